@@ -1,0 +1,137 @@
+/* mpq.h -- C ABI of libmpq: the data-parallel inner loop of sensitivity-guided mixed-precision
+ * post-training quantization, for AMD Instinct MI355X (gfx950).
+ *
+ * Paper: "Mixed Precision Post Training Quantization of Neural Networks with Sensitivity Guided
+ * Search".  The calls below are the per-tensor operations its searches (Alg. 1 bisection, Alg. 2
+ * greedy) and sensitivity metrics (Sec. 3.2) execute over and over: max calibration (Sec. 3.1),
+ * the quantizer of Eq. 1, the error sum inside Eq. 2, the perturbation of Eq. 3-5, and the
+ * quantized linear layer evaluated by "Evaluate f(x, w)".
+ *
+ * Conventions common to every call
+ *  - All data pointers are DEVICE pointers (HIP global memory) unless a comment says "host".
+ *    Scalars (sizes, bits, lambda, seed) are host values.  `stream` is a hipStream_t passed as
+ *    void* (NULL = the default stream).
+ *  - Calls only enqueue work on `stream`; they never synchronise, never copy device<->host and
+ *    never allocate.  Results (absmax, error sums) stay on the device.  The caller owns every
+ *    buffer; scratch comes from the caller's workspace `ws` of `ws_bytes` bytes, whose required
+ *    size is returned by the matching mpq_*_workspace_bytes() (a pure host function).  The
+ *    workspace needs no initialisation, must be 16-byte aligned, and must not be shared by calls
+ *    that may run concurrently.
+ *  - Tensors are dense row-major 2-D [rows x cols] fp32.  `gran` selects the quantization
+ *    granularity: one scale per tensor, per row, or per column.  Linear-layer weights are stored
+ *    [N x K] (out x in, K contiguous), so "per output channel" is MPQ_PER_ROW.
+ *  - Quantizer (Eq. 1 in its symmetric integer form): qmax_b = 2^(b-1) - 1,
+ *    scale_b = fl32(m / qmax_b), inv_b = fl32(qmax_b / m) with m the channel's absmax (both 0
+ *    when m == 0); code = clamp(RNE(x * inv_b), +-qmax_b) where the product is the exact real
+ *    product and RNE is round-half-to-even; Q(x) = fl32(code * scale_b).
+ *  - Inputs must be finite; NaN/Inf give unspecified values (never a fault).
+ *  - Return value: MPQ_OK or an error code below.  Argument errors are detected on the host
+ *    before anything is launched, so a failing call has no effect on the device.
+ */
+#ifndef MPQ_H_
+#define MPQ_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum mpq_status {
+  MPQ_OK = 0,
+  MPQ_ERR_NULL = 1,      /* a required pointer is NULL */
+  MPQ_ERR_SHAPE = 2,     /* dims <= 0, rows*cols overflow, odd cols/K with packed int4, ... */
+  MPQ_ERR_BITS = 3,      /* bit-width outside 2..8, storage bits not 4 or 8, bad range */
+  MPQ_ERR_ALIGN = 4,     /* a pointer lacks the alignment stated for it */
+  MPQ_ERR_WORKSPACE = 5, /* ws is NULL or ws_bytes too small */
+  MPQ_ERR_GRAN = 6,      /* granularity value not valid for this call */
+  MPQ_ERR_HIP = 7        /* the HIP runtime refused a launch; see mpq_last_hip_error() */
+};
+
+enum mpq_gran { MPQ_PER_TENSOR = 0, MPQ_PER_ROW = 1, MPQ_PER_COL = 2 };
+
+/* Text for a status code (static storage, host). */
+const char* mpq_strerror(int status);
+/* Raw hipError_t of the most recent MPQ_ERR_HIP on the calling thread (0 if none). */
+int mpq_last_hip_error(void);
+/* Library version, major*100 + minor. */
+int mpq_version(void);
+
+/* ---- Sec. 3.1, calibration step: m = max |x| --------------------------------------------
+ * x          [rows x cols] fp32, any alignment (16-byte alignment enables 128-bit loads).
+ * gran       PER_TENSOR -> absmax_out[1]; PER_ROW -> [rows]; PER_COL -> [cols].
+ * accumulate 0: absmax_out is overwritten; 1: absmax_out = max(absmax_out, new), the running
+ *            maximum over successive calibration batches (absmax_out must then hold valid
+ *            non-negative values).
+ * No workspace.  The result is exact (max is order independent). */
+int mpq_calibrate_absmax(const float* x, int64_t rows, int64_t cols, int gran, int accumulate,
+                         float* absmax_out, void* stream);
+
+/* scale_out[i] = fl32(absmax[i] / qmax_bits) (0 when absmax[i] == 0), i < count: the step size
+ * of Eq. 1 that mpq_qgemm takes as a_scale / w_scale. */
+int mpq_scale_from_absmax(const float* absmax, int64_t count, int bits, float* scale_out,
+                          void* stream);
+
+/* ---- Sec. 3.1 Eq. 1: b-bit fake quantization ----------------------------------------------
+ * absmax     [1] | [rows] | [cols] according to gran (need not come from the same tensor;
+ *            values beyond it saturate at +-qmax).
+ * bits       2..8.
+ * y_out      nullable: Q(x), fp32 [rows x cols].
+ * codes_out  nullable: integer codes, one int8 per element, [rows x cols].
+ * packed4_out nullable: bits <= 4 only, cols even: two's-complement nibbles, two per byte along
+ *            cols, LOW nibble = even column, HIGH nibble = odd column; [rows x cols/2] bytes.
+ * At least one output must be given.  No workspace. */
+int mpq_fake_quant(const float* x, int64_t rows, int64_t cols, int gran, const float* absmax,
+                   int bits, float* y_out, int8_t* codes_out, uint8_t* packed4_out, void* stream);
+
+/* ---- Sec. 3.2.1 Eq. 2: quantization-error sums for b = b_lo..b_hi in ONE read of x -----------
+ * sse_out    double [nch x nb], channel-major, b ascending; nch = 1 | rows | cols, nb =
+ *            b_hi - b_lo + 1.  sse_out[ch][b] = sum over the channel of (Q_b(x) - x)^2.
+ *            E_QE(b) = sqrt(sse / n) / absmax is left to the host (Eq. 2).
+ * 2 <= b_lo <= b_hi <= 8.  Per-lane partial sums are fp32, combined in double in a fixed order:
+ * results are reproducible run to run and agree with a double-precision sum to ~1e-6 relative. */
+size_t mpq_quant_error_workspace_bytes(int64_t rows, int64_t cols, int gran, int b_lo, int b_hi);
+int mpq_quant_error(const float* x, int64_t rows, int64_t cols, int gran, const float* absmax,
+                    int b_lo, int b_hi, double* sse_out, void* ws, size_t ws_bytes, void* stream);
+
+/* ---- Sec. 3.2.2 Eq. 3-5: Gaussian perturbation ----------------------------------------------
+ * y[i] = fl32(x[i] + sigma_ch * z_i), sigma_ch = fl32(lambda * scale_bits(absmax[ch])): the
+ * noise standard deviation is `lambda` quantization steps of the b-bit grid.  z_i is the i-th
+ * standard normal (i = r*cols + c) of stream `stream_id` under `seed`: Philox-4x32-10 with
+ * key = (seed lo, seed hi), counter = (i/4 lo, i/4 hi, stream_id lo, stream_id hi), output word
+ * pairs (0,1) and (2,3) through Box-Muller with the fixed fp32 log / sin / cos recipes of this
+ * library; z_i depends on (seed, stream_id, i) only -- not on bits, shape or launch geometry.
+ * y_out may alias x.  No workspace. */
+int mpq_noise_inject(const float* x, int64_t rows, int64_t cols, int gran, const float* absmax,
+                     int bits, float lambda, uint64_t seed, uint64_t stream_id, float* y_out,
+                     void* stream);
+
+/* ---- "Evaluate f(x, w)" of Alg. 1 / Alg. 2: one quantized linear layer ------------------------
+ * acc[m][n] = sum_k a_q[m][k] * w_q[n][k] (int32), y[m][n] = fl32(fl32(float(acc) * a_scale[0])
+ *             * w_scale[n or 0]).
+ * a_q        int8 [M x K], K contiguous.
+ * w_q        w_storage_bits == 8: int8 [N x K];  == 4: uint8 [N x K/2] nibble pairs as written
+ *            by mpq_fake_quant (K even).
+ * a_scale    [1]; w_scale [1] (w_gran = PER_TENSOR) or [N] (PER_ROW).  Needed only with y_out.
+ * y_out      nullable fp32 [M x N]; acc_out nullable int32 [M x N]; at least one is required.
+ * K*127*127 must stay below 2^31 (K <= 133143), else MPQ_ERR_SHAPE.
+ * 16-byte aligned a_q / w_q with K a multiple of 16 (32 for packed int4) take the fast path;
+ * anything else is computed by a slower byte-wise loader with identical results.
+ * No workspace is needed at present (ws may be NULL, the query returns 0). */
+size_t mpq_qgemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int w_storage_bits);
+int mpq_qgemm(const int8_t* a_q, const void* w_q, int w_storage_bits, int64_t M, int64_t N,
+              int64_t K, const float* a_scale, const float* w_scale, int w_gran, float* y_out,
+              int32_t* acc_out, void* ws, size_t ws_bytes, void* stream);
+
+/* ---- "save accuracy a" of Alg. 1 / Alg. 2, stand-in score: squared output error ---------------
+ * sse_out[0] = sum_i (y[i] - y_ref[i])^2 (double).  fp32 per-lane partials, fixed-order double
+ * combine.  Dividing by n gives the candidate's output MSE. */
+size_t mpq_sse_pair_workspace_bytes(int64_t n);
+int mpq_sse_pair(const float* y, const float* y_ref, int64_t n, double* sse_out, void* ws,
+                 size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MPQ_H_ */

@@ -1,0 +1,226 @@
+"""Thin Python binding of libmpq (ctypes): the same calls as ``include/mpq.h``, same names.
+
+Argument marshalling only -- every step of the path runs in the HIP kernels of ``libmpq.so``.
+PyTorch is used for device memory and streams, nothing else.  There is no CPU fallback: if the
+library cannot be loaded (or built), importing a symbol from it raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+from . import build as _build
+
+PER_TENSOR, PER_ROW, PER_COL = 0, 1, 2
+OK = 0
+ERR_NULL, ERR_SHAPE, ERR_BITS, ERR_ALIGN, ERR_WORKSPACE, ERR_GRAN, ERR_HIP = 1, 2, 3, 4, 5, 6, 7
+
+EXPORTS = [
+    "mpq_strerror", "mpq_last_hip_error", "mpq_version", "mpq_calibrate_absmax",
+    "mpq_scale_from_absmax", "mpq_fake_quant", "mpq_quant_error_workspace_bytes",
+    "mpq_quant_error", "mpq_noise_inject", "mpq_qgemm_workspace_bytes", "mpq_qgemm",
+    "mpq_sse_pair_workspace_bytes", "mpq_sse_pair",
+]
+
+_lib = None
+
+
+class MpqError(RuntimeError):
+    def __init__(self, status: int, call: str):
+        self.status = status
+        msg = lib().mpq_strerror(status).decode()
+        if status == ERR_HIP:
+            msg += " (hipError %d)" % lib().mpq_last_hip_error()
+        super().__init__("%s: %s" % (call, msg))
+
+
+def lib():
+    """Loads libmpq.so (built in-tree); builds it first only if no built library exists."""
+    global _lib
+    if _lib is None:
+        path = _build.LIB
+        if not os.path.exists(path):
+            _build.build_lib()
+        L = C.CDLL(path)
+        vp, i64, ci, sz = C.c_void_p, C.c_int64, C.c_int, C.c_size_t
+        L.mpq_strerror.restype = C.c_char_p
+        L.mpq_strerror.argtypes = [ci]
+        L.mpq_last_hip_error.restype = ci
+        L.mpq_version.restype = ci
+        L.mpq_calibrate_absmax.argtypes = [vp, i64, i64, ci, ci, vp, vp]
+        L.mpq_scale_from_absmax.argtypes = [vp, i64, ci, vp, vp]
+        L.mpq_fake_quant.argtypes = [vp, i64, i64, ci, vp, ci, vp, vp, vp, vp]
+        L.mpq_quant_error_workspace_bytes.restype = sz
+        L.mpq_quant_error_workspace_bytes.argtypes = [i64, i64, ci, ci, ci]
+        L.mpq_quant_error.argtypes = [vp, i64, i64, ci, vp, ci, ci, vp, vp, sz, vp]
+        L.mpq_noise_inject.argtypes = [vp, i64, i64, ci, vp, ci, C.c_float, C.c_uint64, C.c_uint64, vp, vp]
+        L.mpq_qgemm_workspace_bytes.restype = sz
+        L.mpq_qgemm_workspace_bytes.argtypes = [i64, i64, i64, ci]
+        L.mpq_qgemm.argtypes = [vp, vp, ci, i64, i64, i64, vp, vp, ci, vp, vp, vp, sz, vp]
+        L.mpq_sse_pair_workspace_bytes.restype = sz
+        L.mpq_sse_pair_workspace_bytes.argtypes = [i64]
+        L.mpq_sse_pair.argtypes = [vp, vp, i64, vp, vp, sz, vp]
+        for name in EXPORTS:
+            getattr(L, name)  # raises AttributeError if the library lacks a declared symbol
+        _lib = L
+    return _lib
+
+
+def _check(status: int, call: str):
+    if status != OK:
+        raise MpqError(status, call)
+
+
+# ---------------------------------------------------------------------------------------------
+# torch plumbing (device buffers and the current stream)
+def _torch():
+    import torch
+    return torch
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    return _torch().cuda.current_stream().cuda_stream
+
+
+def _dev2d(x, dtype):
+    torch = _torch()
+    if not x.is_cuda:
+        raise ValueError("libmpq works on device tensors")
+    if x.dim() != 2 or x.dtype != dtype or not x.is_contiguous():
+        raise ValueError("expected a contiguous 2-D %s tensor" % dtype)
+    return x
+
+
+def _nch(gran, rows, cols):
+    return {PER_TENSOR: 1, PER_ROW: rows, PER_COL: cols}[gran]
+
+
+class Workspace:
+    """A growable device scratch buffer handed to the calls that need one."""
+
+    def __init__(self):
+        self.buf = None
+
+    def get(self, nbytes: int):
+        torch = _torch()
+        if nbytes == 0:
+            return None, 0
+        if self.buf is None or self.buf.numel() < nbytes:
+            self.buf = torch.empty(max(nbytes, 1 << 16), dtype=torch.uint8, device="cuda")
+        return self.buf.data_ptr(), self.buf.numel()
+
+
+_default_ws = Workspace()
+
+
+# ---------------------------------------------------------------------------------------------
+def calibrate_absmax(x, gran=PER_TENSOR, out=None, accumulate=False):
+    torch = _torch()
+    x = _dev2d(x, torch.float32)
+    rows, cols = x.shape
+    if out is None:
+        if accumulate:
+            raise ValueError("accumulate needs the running absmax in `out`")
+        out = torch.empty(_nch(gran, rows, cols), dtype=torch.float32, device=x.device)
+    _check(lib().mpq_calibrate_absmax(_ptr(x), rows, cols, gran, int(accumulate), _ptr(out),
+                                      _stream()), "mpq_calibrate_absmax")
+    return out
+
+
+def scale_from_absmax(absmax, bits, out=None):
+    torch = _torch()
+    if out is None:
+        out = torch.empty_like(absmax)
+    _check(lib().mpq_scale_from_absmax(_ptr(absmax), absmax.numel(), bits, _ptr(out), _stream()),
+           "mpq_scale_from_absmax")
+    return out
+
+
+def fake_quant(x, absmax, bits, gran=PER_TENSOR, want_y=True, want_codes=False, want_packed4=False,
+               y=None, codes=None, packed4=None):
+    """Returns (y | None, codes | None, packed4 | None)."""
+    torch = _torch()
+    x = _dev2d(x, torch.float32)
+    rows, cols = x.shape
+    if want_y and y is None:
+        y = torch.empty_like(x)
+    if want_codes and codes is None:
+        codes = torch.empty((rows, cols), dtype=torch.int8, device=x.device)
+    if want_packed4 and packed4 is None:
+        packed4 = torch.empty((rows, cols // 2), dtype=torch.uint8, device=x.device)
+    _check(lib().mpq_fake_quant(_ptr(x), rows, cols, gran, _ptr(absmax), bits, _ptr(y), _ptr(codes),
+                                _ptr(packed4), _stream()), "mpq_fake_quant")
+    return y, codes, packed4
+
+
+def quant_error_workspace_bytes(rows, cols, gran=PER_TENSOR, b_lo=2, b_hi=8) -> int:
+    return int(lib().mpq_quant_error_workspace_bytes(rows, cols, gran, b_lo, b_hi))
+
+
+def quant_error(x, absmax, b_lo=2, b_hi=8, gran=PER_TENSOR, out=None, ws: Workspace = None):
+    """Returns float64 [nch, nb] on the device."""
+    torch = _torch()
+    x = _dev2d(x, torch.float32)
+    rows, cols = x.shape
+    nb = b_hi - b_lo + 1
+    if out is None:
+        out = torch.empty((_nch(gran, rows, cols), max(nb, 1)), dtype=torch.float64, device=x.device)
+    wp, wn = (ws or _default_ws).get(quant_error_workspace_bytes(rows, cols, gran, b_lo, b_hi))
+    _check(lib().mpq_quant_error(_ptr(x), rows, cols, gran, _ptr(absmax), b_lo, b_hi, _ptr(out), wp,
+                                 wn, _stream()), "mpq_quant_error")
+    return out
+
+
+def noise_inject(x, absmax, bits, lam, seed, stream_id, gran=PER_TENSOR, out=None):
+    torch = _torch()
+    x = _dev2d(x, torch.float32)
+    rows, cols = x.shape
+    if out is None:
+        out = torch.empty_like(x)
+    _check(lib().mpq_noise_inject(_ptr(x), rows, cols, gran, _ptr(absmax), bits, float(lam),
+                                  int(seed), int(stream_id), _ptr(out), _stream()), "mpq_noise_inject")
+    return out
+
+
+def qgemm_workspace_bytes(M, N, K, w_storage_bits=8) -> int:
+    return int(lib().mpq_qgemm_workspace_bytes(M, N, K, w_storage_bits))
+
+
+def qgemm(a_q, w_q, a_scale, w_scale, w_storage_bits=8, w_gran=PER_TENSOR, want_y=True,
+          want_acc=False, y=None, acc=None, ws: Workspace = None):
+    """Returns (Y fp32 [M,N] | None, acc int32 [M,N] | None)."""
+    torch = _torch()
+    a_q = _dev2d(a_q, torch.int8)
+    M, K = a_q.shape
+    N = w_q.shape[0]
+    if want_y and y is None:
+        y = torch.empty((M, N), dtype=torch.float32, device=a_q.device)
+    if want_acc and acc is None:
+        acc = torch.empty((M, N), dtype=torch.int32, device=a_q.device)
+    wp, wn = (ws or _default_ws).get(qgemm_workspace_bytes(M, N, K, w_storage_bits))
+    _check(lib().mpq_qgemm(_ptr(a_q), _ptr(w_q), w_storage_bits, M, N, K, _ptr(a_scale),
+                           _ptr(w_scale), w_gran, _ptr(y), _ptr(acc), wp, wn, _stream()), "mpq_qgemm")
+    return y, acc
+
+
+def sse_pair_workspace_bytes(n) -> int:
+    return int(lib().mpq_sse_pair_workspace_bytes(n))
+
+
+def sse_pair(y, y_ref, out=None, ws: Workspace = None):
+    torch = _torch()
+    n = y.numel()
+    if y_ref.numel() != n or y.dtype != torch.float32 or y_ref.dtype != torch.float32:
+        raise ValueError("sse_pair needs two fp32 tensors of equal size")
+    if not (y.is_contiguous() and y_ref.is_contiguous()):
+        raise ValueError("sse_pair needs contiguous tensors")
+    if out is None:
+        out = torch.empty(1, dtype=torch.float64, device=y.device)
+    wp, wn = (ws or _default_ws).get(sse_pair_workspace_bytes(n))
+    _check(lib().mpq_sse_pair(_ptr(y), _ptr(y_ref), n, _ptr(out), wp, wn, _stream()), "mpq_sse_pair")
+    return out

@@ -1,0 +1,157 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every function the
+header declares, and rejects bad arguments before launching anything."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2302_01382_amd import mpq
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = C.c_void_p(0x1000)   # never dereferenced: validation fails first
+FAKE16 = C.c_void_p(0x10000)
+
+
+def _no_gpu() -> bool:
+    try:
+        import torch
+        return not torch.cuda.is_available()
+    except Exception:
+        return True
+
+
+# calls with made-up pointers are only ever issued where nothing could be launched
+needs_no_gpu = pytest.mark.skipif(not _no_gpu(), reason="fake-pointer validation runs on GPU-less hosts only")
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "mpq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mpq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert len(names) >= 13
+    L = mpq.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(mpq.EXPORTS) == names
+
+
+def test_binding_module_has_the_same_names():
+    for n in declared_functions():
+        short = n[len("mpq_"):]
+        if short in ("strerror", "last_hip_error", "version"):
+            continue
+        assert hasattr(mpq, short), short
+
+
+def test_strerror_and_version():
+    L = mpq.lib()
+    assert L.mpq_version() >= 100
+    seen = set()
+    for code in range(0, 8):
+        s = L.mpq_strerror(code).decode()
+        assert s and s not in seen
+        seen.add(s)
+    assert "unknown" in L.mpq_strerror(99).decode()
+
+
+@needs_no_gpu
+def test_calibrate_absmax_validation():
+    L = mpq.lib()
+    f = L.mpq_calibrate_absmax
+    assert f(None, 4, 4, 0, 0, FAKE, None) == mpq.ERR_NULL
+    assert f(FAKE, 4, 4, 0, 0, None, None) == mpq.ERR_NULL
+    assert f(FAKE, 0, 4, 0, 0, FAKE, None) == mpq.ERR_SHAPE
+    assert f(FAKE, 4, -1, 0, 0, FAKE, None) == mpq.ERR_SHAPE
+    assert f(FAKE, 2 ** 40, 2 ** 40, 0, 0, FAKE, None) == mpq.ERR_SHAPE
+    assert f(FAKE, 4, 4, 3, 0, FAKE, None) == mpq.ERR_GRAN
+    assert L.mpq_scale_from_absmax(FAKE, 4, 9, FAKE, None) == mpq.ERR_BITS
+    assert L.mpq_scale_from_absmax(FAKE, 0, 8, FAKE, None) == mpq.ERR_SHAPE
+    assert L.mpq_scale_from_absmax(None, 4, 8, FAKE, None) == mpq.ERR_NULL
+
+
+@needs_no_gpu
+def test_fake_quant_validation():
+    f = mpq.lib().mpq_fake_quant
+    assert f(None, 4, 4, 0, FAKE, 4, FAKE, None, None, None) == mpq.ERR_NULL
+    assert f(FAKE, 4, 4, 0, None, 4, FAKE, None, None, None) == mpq.ERR_NULL
+    assert f(FAKE, 4, 4, 0, FAKE, 4, None, None, None, None) == mpq.ERR_NULL  # no output at all
+    assert f(FAKE, 4, 4, 0, FAKE, 1, FAKE, None, None, None) == mpq.ERR_BITS
+    assert f(FAKE, 4, 4, 0, FAKE, 9, FAKE, None, None, None) == mpq.ERR_BITS
+    assert f(FAKE, 4, 4, 0, FAKE, 5, None, None, FAKE, None) == mpq.ERR_BITS  # packed needs <= 4
+    assert f(FAKE, 4, 5, 0, FAKE, 4, None, None, FAKE, None) == mpq.ERR_SHAPE  # odd cols, packed
+    assert f(FAKE, 4, 4, 7, FAKE, 4, FAKE, None, None, None) == mpq.ERR_GRAN
+    assert f(FAKE, -4, 4, 0, FAKE, 4, FAKE, None, None, None) == mpq.ERR_SHAPE
+
+
+@needs_no_gpu
+def test_quant_error_validation_and_workspace_query():
+    L = mpq.lib()
+    f = L.mpq_quant_error
+    q = L.mpq_quant_error_workspace_bytes
+    assert q(0, 4, 0, 2, 8) == 0 and q(4, 4, 0, 1, 8) == 0 and q(4, 4, 5, 2, 8) == 0
+    need = q(1000, 1000, 0, 2, 8)
+    assert need > 0 and need % 8 == 0
+    assert q(1000, 1000, 1, 2, 8) == 0                      # one wave covers a row: no scratch
+    assert q(4, 100000, 1, 2, 8) == 4 * 7 * 7 * 8           # 7 segments per row
+    assert q(1000, 1000, 2, 2, 8) >= 1000 * 7 * 8
+    assert f(None, 4, 4, 0, FAKE, 2, 8, FAKE, FAKE16, 1 << 20, None) == mpq.ERR_NULL
+    assert f(FAKE, 4, 4, 0, FAKE, 2, 8, None, FAKE16, 1 << 20, None) == mpq.ERR_NULL
+    assert f(FAKE, 4, 4, 0, FAKE, 1, 8, FAKE, FAKE16, 1 << 20, None) == mpq.ERR_BITS
+    assert f(FAKE, 4, 4, 0, FAKE, 5, 4, FAKE, FAKE16, 1 << 20, None) == mpq.ERR_BITS
+    assert f(FAKE, 4, 4, 0, FAKE, 2, 9, FAKE, FAKE16, 1 << 20, None) == mpq.ERR_BITS
+    assert f(FAKE, 1000, 1000, 0, FAKE, 2, 8, FAKE, None, 0, None) == mpq.ERR_WORKSPACE
+    assert f(FAKE, 1000, 1000, 0, FAKE, 2, 8, FAKE, FAKE16, need - 1, None) == mpq.ERR_WORKSPACE
+    assert f(FAKE, 1000, 1000, 0, FAKE, 2, 8, FAKE, C.c_void_p(0x10008), need, None) == mpq.ERR_ALIGN
+    assert f(FAKE, 1000, 1000, 0, FAKE, 2, 8, C.c_void_p(0x1004), FAKE16, need, None) == mpq.ERR_ALIGN
+    assert f(FAKE, 4, 4, 4, FAKE, 2, 8, FAKE, FAKE16, 1 << 20, None) == mpq.ERR_GRAN
+
+
+@needs_no_gpu
+def test_noise_validation():
+    f = mpq.lib().mpq_noise_inject
+    assert f(None, 4, 4, 0, FAKE, 4, 0.5, 1, 2, FAKE, None) == mpq.ERR_NULL
+    assert f(FAKE, 4, 4, 0, FAKE, 4, 0.5, 1, 2, None, None) == mpq.ERR_NULL
+    assert f(FAKE, 4, 4, 0, FAKE, 0, 0.5, 1, 2, FAKE, None) == mpq.ERR_BITS
+    assert f(FAKE, 4, 0, 0, FAKE, 4, 0.5, 1, 2, FAKE, None) == mpq.ERR_SHAPE
+    assert f(FAKE, 4, 4, -1, FAKE, 4, 0.5, 1, 2, FAKE, None) == mpq.ERR_GRAN
+
+
+@needs_no_gpu
+def test_qgemm_validation():
+    L = mpq.lib()
+    f = L.mpq_qgemm
+    assert L.mpq_qgemm_workspace_bytes(128, 128, 128, 8) == 0
+    ok_tail = (FAKE, FAKE, 0, FAKE, None, None, 0, None)
+    assert f(None, FAKE, 8, 4, 4, 16, *ok_tail) == mpq.ERR_NULL
+    assert f(FAKE, None, 8, 4, 4, 16, *ok_tail) == mpq.ERR_NULL
+    assert f(FAKE, FAKE, 8, 4, 4, 16, FAKE, FAKE, 0, None, None, None, 0, None) == mpq.ERR_NULL
+    assert f(FAKE, FAKE, 8, 4, 4, 16, None, FAKE, 0, FAKE, None, None, 0, None) == mpq.ERR_NULL
+    assert f(FAKE, FAKE, 6, 4, 4, 16, *ok_tail) == mpq.ERR_BITS
+    assert f(FAKE, FAKE, 8, 0, 4, 16, *ok_tail) == mpq.ERR_SHAPE
+    assert f(FAKE, FAKE, 4, 4, 4, 15, *ok_tail) == mpq.ERR_SHAPE       # odd K with packed int4
+    assert f(FAKE, FAKE, 8, 4, 4, 133144, *ok_tail) == mpq.ERR_SHAPE   # int32 could overflow
+    assert f(FAKE, FAKE, 8, 4, 4, 16, FAKE, FAKE, 2, FAKE, None, None, 0, None) == mpq.ERR_GRAN
+    assert f(FAKE, FAKE, 8, 4, 4, 16, FAKE, FAKE, 0, C.c_void_p(0x1002), None, None, 0, None) == mpq.ERR_ALIGN
+
+
+@needs_no_gpu
+def test_sse_pair_validation():
+    L = mpq.lib()
+    f = L.mpq_sse_pair
+    need = L.mpq_sse_pair_workspace_bytes(1 << 20)
+    assert need > 0 and L.mpq_sse_pair_workspace_bytes(0) == 0
+    assert f(None, FAKE, 16, FAKE, FAKE16, need, None) == mpq.ERR_NULL
+    assert f(FAKE, FAKE, 0, FAKE, FAKE16, need, None) == mpq.ERR_SHAPE
+    assert f(FAKE16, FAKE16, 1 << 20, FAKE, None, 0, None) == mpq.ERR_WORKSPACE
+    assert f(FAKE16, FAKE16, 1 << 20, FAKE, FAKE16, need - 8, None) == mpq.ERR_WORKSPACE
+
+
+def test_python_errors_carry_the_message():
+    with pytest.raises(mpq.MpqError) as e:
+        mpq._check(mpq.ERR_BITS, "mpq_fake_quant")
+    assert "bit-width" in str(e.value) and e.value.status == mpq.ERR_BITS
