@@ -157,7 +157,8 @@ int orc_fake_quant(const float* x, int64_t rows, int64_t cols, int gran, const f
 
 // ------------------------------------------------------------------------------------------
 // Eq. 2, the sum under the expectation: SSE_b = sum (Q_b(x) - x)^2 for every b in b_lo..b_hi,
-// per tensor or per channel, accumulated in double in index order.
+// per tensor or per channel, accumulated in double in index order.  Q_b(x) = code * scale_b is
+// taken exactly (the fp32 constants scale_b, inv_b are the only roundings in the definition).
 // sse is [nch][nb], channel-major, b ascending.
 int orc_quant_error(const float* x, int64_t rows, int64_t cols, int gran, const float* absmax,
                     int b_lo, int b_hi, double* sse) {
@@ -177,8 +178,10 @@ int orc_quant_error(const float* x, int64_t rows, int64_t cols, int gran, const 
       const float xv = x[r * cols + c];
       for (int b = b_lo; b <= b_hi; ++b) {
         const int64_t kb = ch * nb + (b - b_lo);
-        const float qx = dequant_of(code_of(xv, inv[kb], orc_qmax(b)), scale[kb]);
-        const double e = (double)qx - (double)xv;
+        // Eq. 2 is stated over the reals: Q(x) here is the grid point code * scale_b itself
+        // (exact in double: 8 x 24 significant bits), not its rounding to fp32.
+        const double qx = (double)code_of(xv, inv[kb], orc_qmax(b)) * (double)scale[kb];
+        const double e = qx - (double)xv;
         sse[ch * nb + (b - b_lo)] += e * e;
       }
     }

@@ -193,9 +193,14 @@ def test_sse_brute_force_closed_form_and_invariances():
     sse = oracle.quant_error(x, m)
     assert sse.shape == (1, 7)
     for i, b in enumerate(range(2, 9)):
-        y, _, _ = oracle.fake_quant(x, m, b)
-        brute = math.fsum(((y.astype(np.float64) - x.astype(np.float64)) ** 2).ravel().tolist())
+        y, c, _ = oracle.fake_quant(x, m, b)
+        s_b, _ = oracle.bit_constants(float(m[0]), b)
+        grid = c.astype(np.float64) * np.float64(s_b)       # the grid point, exactly
+        brute = math.fsum(((grid - x.astype(np.float64)) ** 2).ravel().tolist())
         assert sse[0, i] == pytest.approx(brute, rel=1e-12)
+        # the fp32 dequantized tensor is that grid point rounded once: same sum to ~1e-5
+        viay = math.fsum(((y.astype(np.float64) - x.astype(np.float64)) ** 2).ravel().tolist())
+        assert sse[0, i] == pytest.approx(viay, rel=1e-4)
     # dense uniform data on a fine grid: mean squared rounding error -> step^2 / 12
     s8, _ = oracle.bit_constants(float(m[0]), 8)
     assert sse[0, 6] / x.size == pytest.approx(float(s8) ** 2 / 12, rel=0.02)
