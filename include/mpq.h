@@ -64,9 +64,12 @@ int mpq_version(void);
  * accumulate 0: absmax_out is overwritten; 1: absmax_out = max(absmax_out, new), the running
  *            maximum over successive calibration batches (absmax_out must then hold valid
  *            non-negative values).
- * No workspace.  The result is exact (max is order independent). */
+ * Workspace: needed for PER_TENSOR only (one partial maximum per workgroup); the query returns 0
+ * for the other granularities and ws may then be NULL.
+ * The result is exact (max is order independent). */
+size_t mpq_calibrate_absmax_workspace_bytes(int64_t rows, int64_t cols, int gran);
 int mpq_calibrate_absmax(const float* x, int64_t rows, int64_t cols, int gran, int accumulate,
-                         float* absmax_out, void* stream);
+                         float* absmax_out, void* ws, size_t ws_bytes, void* stream);
 
 /* scale_out[i] = fl32(absmax[i] / qmax_bits) (0 when absmax[i] == 0), i < count: the step size
  * of Eq. 1 that mpq_qgemm takes as a_scale / w_scale. */

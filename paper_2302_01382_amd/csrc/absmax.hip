@@ -1,9 +1,12 @@
 // absmax.hip -- max calibration (paper Sec. 3.1, first step of scale estimation): m = max |x|
 // per tensor, per row or per column.  HBM-bound: 4 bytes read per element, one v_max per element.
 //
-// |x| >= 0, so its bit pattern orders like its value: blocks combine with an integer atomic max,
-// which is exact and order independent.  accumulate == 0 first clears the output with a fill
-// kernel (not a memset node, so the call can be captured in a HIP graph).
+// Per tensor: every block writes one partial maximum to the workspace and a one-block kernel
+// folds them (and the previous value when accumulating) -- thousands of atomics on ONE address
+// serialise in L2 and cost ~10 us.  Per row / per column the outputs are many addresses: |x| >= 0,
+// so its bit pattern orders like its value and blocks combine with an integer atomic max (exact,
+// order independent) after a fill kernel cleared the output (a kernel, not a memset node, so the
+// call can be captured in a HIP graph).
 #include "common.hpp"
 
 namespace mpq {
@@ -13,28 +16,19 @@ __global__ void fill_u32(unsigned* p, int64_t n, unsigned v) {
   if (i < n) p[i] = v;
 }
 
-// flat tensor, 128-bit loads when VEC, four loads in flight per lane
+// flat tensor: contiguous 16 KiB tiles dealt round-robin when VEC, scalar grid-stride otherwise
+// partials: float [gridDim.x]
 template <bool VEC>
 __global__ __launch_bounds__(kBlock) void absmax_flat(const float* __restrict__ x, int64_t n,
-                                                      unsigned* __restrict__ out) {
+                                                      float* __restrict__ partials) {
   const int64_t tid = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   const int64_t nthr = (int64_t)gridDim.x * kBlock;
   float m = 0.0f;
   if (VEC) {
-    const float4* x4 = reinterpret_cast<const float4*>(x);
     const int64_t n4 = n >> 2;
-    int64_t i = tid;
-    for (; i + 3 * nthr < n4; i += 4 * nthr) {
-      const float4 a = x4[i], b = x4[i + nthr], c = x4[i + 2 * nthr], d = x4[i + 3 * nthr];
+    for_each_vec4_tiled(reinterpret_cast<const float4*>(x), n4, [&](const float4 a, int64_t) {
       m = fmaxf(m, fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))));
-      m = fmaxf(m, fmaxf(fmaxf(fabsf(b.x), fabsf(b.y)), fmaxf(fabsf(b.z), fabsf(b.w))));
-      m = fmaxf(m, fmaxf(fmaxf(fabsf(c.x), fabsf(c.y)), fmaxf(fabsf(c.z), fabsf(c.w))));
-      m = fmaxf(m, fmaxf(fmaxf(fabsf(d.x), fabsf(d.y)), fmaxf(fabsf(d.z), fabsf(d.w))));
-    }
-    for (; i < n4; i += nthr) {
-      const float4 a = x4[i];
-      m = fmaxf(m, fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))));
-    }
+    });
     for (int64_t j = (n4 << 2) + tid; j < n; j += nthr) m = fmaxf(m, fabsf(x[j]));
   } else {
     for (int64_t j = tid; j < n; j += nthr) m = fmaxf(m, fabsf(x[j]));
@@ -43,16 +37,30 @@ __global__ __launch_bounds__(kBlock) void absmax_flat(const float* __restrict__ 
   __shared__ float sm[kBlock / kWave];
   if ((threadIdx.x & (kWave - 1)) == 0) sm[threadIdx.x / kWave] = m;
   __syncthreads();
+  if (threadIdx.x == 0) partials[blockIdx.x] = fmaxf(fmaxf(sm[0], sm[1]), fmaxf(sm[2], sm[3]));
+}
+
+__global__ __launch_bounds__(kBlock) void absmax_finish(const float* __restrict__ partials, int np,
+                                                        int accumulate, float* __restrict__ out) {
+  float m = 0.0f;
+#pragma unroll 8
+  for (int p = threadIdx.x; p < np; p += kBlock) m = fmaxf(m, partials[p]);
+  m = wave_max(m);
+  __shared__ float sm[kBlock / kWave];
+  if ((threadIdx.x & (kWave - 1)) == 0) sm[threadIdx.x / kWave] = m;
+  __syncthreads();
   if (threadIdx.x == 0) {
-    const float b = fmaxf(fmaxf(sm[0], sm[1]), fmaxf(sm[2], sm[3]));
-    atomicMax(out, abs_key(b));
+    float b = fmaxf(fmaxf(sm[0], sm[1]), fmaxf(sm[2], sm[3]));
+    if (accumulate) b = fmaxf(b, out[0]);
+    out[0] = b;
   }
 }
 
 // per row: one wave per (row, segment of kSeg columns)
 constexpr int64_t kSeg = 16384;
 
-template <bool VEC>
+// DIRECT: one segment per row and no running maximum -> plain store, no clearing pass needed
+template <bool VEC, bool DIRECT>
 __global__ __launch_bounds__(kBlock) void absmax_rows(const float* __restrict__ x, int64_t rows,
                                                       int64_t cols, int64_t nseg,
                                                       unsigned* __restrict__ out) {
@@ -74,7 +82,10 @@ __global__ __launch_bounds__(kBlock) void absmax_rows(const float* __restrict__ 
     for (int64_t c = c0 + lane; c < c1; c += kWave) m = fmaxf(m, fabsf(row[c]));
   }
   m = wave_max(m);
-  if (lane == 0) atomicMax(out + r, abs_key(m));  // a max even with one segment: honours accumulate
+  if (lane == 0) {
+    if (DIRECT) out[r] = abs_key(m);
+    else atomicMax(out + r, abs_key(m));
+  }
 }
 
 // per column: a lane owns 4 adjacent columns (VEC) or one column; waves of a block take
@@ -119,31 +130,52 @@ __global__ void scale_from_absmax_k(const float* __restrict__ absmax, int64_t co
 
 using namespace mpq;
 
+static unsigned absmax_flat_grid(int64_t n, bool vec) {
+  return vec ? flat_grid(n >> 2, kBlock * kTileVec) : flat_grid(n, kBlock * 4);
+}
+
+extern "C" size_t mpq_calibrate_absmax_workspace_bytes(int64_t rows, int64_t cols, int gran) {
+  if (rows <= 0 || cols <= 0 || mul_overflows(rows, cols) || gran != MPQ_PER_TENSOR) return 0;
+  const unsigned a = absmax_flat_grid(rows * cols, true), b = absmax_flat_grid(rows * cols, false);
+  return (size_t)(a > b ? a : b) * sizeof(float);
+}
+
 extern "C" int mpq_calibrate_absmax(const float* x, int64_t rows, int64_t cols, int gran,
-                                    int accumulate, float* absmax_out, void* stream) {
+                                    int accumulate, float* absmax_out, void* ws, size_t ws_bytes,
+                                    void* stream) {
   if (!x || !absmax_out) return MPQ_ERR_NULL;
   if (rows <= 0 || cols <= 0 || mul_overflows(rows, cols)) return MPQ_ERR_SHAPE;
   if (gran < MPQ_PER_TENSOR || gran > MPQ_PER_COL) return MPQ_ERR_GRAN;
+  if (gran == MPQ_PER_TENSOR) {
+    if (!ws || ws_bytes < mpq_calibrate_absmax_workspace_bytes(rows, cols, gran)) return MPQ_ERR_WORKSPACE;
+    if (!aligned16(ws)) return MPQ_ERR_ALIGN;
+  }
   hipStream_t st = (hipStream_t)stream;
   unsigned* out = reinterpret_cast<unsigned*>(absmax_out);
   const int64_t nch = channels(gran, rows, cols);
   const int64_t n = rows * cols;
-  if (!accumulate) {
+  const int64_t nseg = (cols + kSeg - 1) / kSeg;
+  const bool direct = gran == MPQ_PER_ROW && nseg == 1 && !accumulate;
+  if (!accumulate && !direct && gran != MPQ_PER_TENSOR) {
     fill_u32<<<(unsigned)((nch + 255) / 256), 256, 0, st>>>(out, nch, 0u);
   }
   const bool a16 = aligned16(x);
   if (gran == MPQ_PER_TENSOR) {
-    if (a16) absmax_flat<true><<<flat_grid(n >> 2, 4), kBlock, 0, st>>>(x, n, out);
-    else absmax_flat<false><<<flat_grid(n, 4), kBlock, 0, st>>>(x, n, out);
+    const unsigned g = absmax_flat_grid(n, a16);
+    float* partials = reinterpret_cast<float*>(ws);
+    if (a16) absmax_flat<true><<<g, kBlock, 0, st>>>(x, n, partials);
+    else absmax_flat<false><<<g, kBlock, 0, st>>>(x, n, partials);
+    absmax_finish<<<1, kBlock, 0, st>>>(partials, (int)g, accumulate, absmax_out);
   } else if (gran == MPQ_PER_ROW) {
-    const int64_t nseg = (cols + kSeg - 1) / kSeg;
     const int64_t items = rows * nseg;
     const int64_t blocks = (items + kBlock / kWave - 1) / (kBlock / kWave);
     if (blocks > 0x7FFFFFFF) return MPQ_ERR_SHAPE;
-    if (a16 && (cols & 3) == 0)
-      absmax_rows<true><<<(unsigned)blocks, kBlock, 0, st>>>(x, rows, cols, nseg, out);
-    else
-      absmax_rows<false><<<(unsigned)blocks, kBlock, 0, st>>>(x, rows, cols, nseg, out);
+    const bool vec = a16 && (cols & 3) == 0;
+    const unsigned g = (unsigned)blocks;
+    if (vec && direct) absmax_rows<true, true><<<g, kBlock, 0, st>>>(x, rows, cols, nseg, out);
+    else if (vec) absmax_rows<true, false><<<g, kBlock, 0, st>>>(x, rows, cols, nseg, out);
+    else if (direct) absmax_rows<false, true><<<g, kBlock, 0, st>>>(x, rows, cols, nseg, out);
+    else absmax_rows<false, false><<<g, kBlock, 0, st>>>(x, rows, cols, nseg, out);
   } else {
     const bool vec = a16 && (cols & 3) == 0;
     const int64_t cols_per_block = vec ? kWave * 4 : kWave;

@@ -36,17 +36,25 @@ inline int64_t channels(int gran, int64_t rows, int64_t cols) {
   return gran == MPQ_PER_ROW ? rows : gran == MPQ_PER_COL ? cols : 1;
 }
 
-// grid for a flat streaming kernel: enough blocks to fill the chip several times over, never more
-// than the work, so that a lane accumulates at most a few hundred elements in fp32.
-inline unsigned flat_grid(int64_t vec_items, int items_per_thread, int blocks_per_cu = 8) {
-  int64_t want = (vec_items + (int64_t)kBlock * items_per_thread - 1) / ((int64_t)kBlock * items_per_thread);
-  int64_t cap = (int64_t)kNumCU * blocks_per_cu;
-  // very large tensors: let the grid grow so a lane never sums more than ~1024 vectors
-  int64_t min_for_len = (vec_items + (int64_t)kBlock * 1024 - 1) / ((int64_t)kBlock * 1024);
-  if (cap < min_for_len) cap = min_for_len;
-  if (want > cap) want = cap;
-  if (want < 1) want = 1;
-  return (unsigned)want;
+// Flat streaming kernels walk the tensor in tiles of kTileVec float4 per lane x kBlock lanes
+// (16 KiB contiguous), all kTileVec loads issued before the first use; tiles are dealt round-robin
+// to a persistent grid whose size divides the tile count evenly (every block gets the same number
+// of tiles, so the grid finishes together).  Measured on MI355X, contiguous tiles read ~6.1 TB/s
+// from HBM against ~5.3 TB/s for a plain grid-stride loop; for kernels that also write, round-robin
+// tiles beat one contiguous span per block by ~10 %.
+constexpr int kTileVec = 4;
+
+// grid for a flat streaming kernel over `units` work items (float4 vectors or scalars) of which a
+// block takes `units_per_trip` per trip: about blocks_per_cu blocks per CU, every block the same
+// number of trips r (the last block may fall short), r capped at 256 so that a lane never
+// accumulates more than 256 trips in fp32.
+inline unsigned flat_grid(int64_t units, int64_t units_per_trip, int blocks_per_cu = 8) {
+  const int64_t trips = (units + units_per_trip - 1) / units_per_trip;
+  if (trips <= 1) return 1;
+  const int64_t cap = (int64_t)kNumCU * blocks_per_cu;
+  int64_t r = (trips + cap - 1) / cap;  // trips per block
+  if (r > 256) r = 256;
+  return (unsigned)((trips + r - 1) / r);
 }
 
 // ---- device side ---------------------------------------------------------------------------
@@ -111,6 +119,52 @@ __device__ __forceinline__ float code_f(float x, float inv, float qmax) {
   const float t = __builtin_fmaf(x, inv, kMagic);
   const float q = t - kMagic;
   return __builtin_amdgcn_fmed3f(q, -qmax, qmax);
+}
+
+// Visits every float4 of x4[0, n4) that the tile round-robin deals to this block: f(value, index).
+template <typename F>
+__device__ __forceinline__ void for_each_vec4_tiled(const float4* __restrict__ x4, int64_t n4, F&& f) {
+  constexpr int64_t tile = (int64_t)kBlock * kTileVec;
+  const int64_t ntiles = (n4 + tile - 1) / tile;
+  for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+    const int64_t base = t * tile + threadIdx.x;
+    if ((t + 1) * tile <= n4) {  // block-uniform
+      float4 v[kTileVec];
+#pragma unroll
+      for (int u = 0; u < kTileVec; ++u) v[u] = x4[base + u * kBlock];
+#pragma unroll
+      for (int u = 0; u < kTileVec; ++u) f(v[u], base + u * kBlock);
+    } else {
+#pragma unroll
+      for (int u = 0; u < kTileVec; ++u) {
+        const int64_t i = base + u * kBlock;
+        if (i < n4) f(x4[i], i);
+      }
+    }
+  }
+}
+
+// Same walk over two tensors at once: f(a, b); two + two loads in flight.
+template <typename F>
+__device__ __forceinline__ void for_each_vec4_pair_tiled(const float4* __restrict__ a4,
+                                                         const float4* __restrict__ b4, int64_t n4, F&& f) {
+  constexpr int U = 2;
+  constexpr int64_t tile = (int64_t)kBlock * U;
+  const int64_t ntiles = (n4 + tile - 1) / tile;
+  for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+    const int64_t base = t * tile + threadIdx.x;
+    if ((t + 1) * tile <= n4) {
+      const float4 a0 = a4[base], b0 = b4[base], a1 = a4[base + kBlock], b1 = b4[base + kBlock];
+      f(a0, b0);
+      f(a1, b1);
+    } else {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int64_t i = base + u * kBlock;
+        if (i < n4) f(a4[i], b4[i]);
+      }
+    }
+  }
 }
 
 // |x| as an unsigned key: for non-negative floats the bit pattern orders like the value, so an

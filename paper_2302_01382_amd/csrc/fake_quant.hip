@@ -56,18 +56,9 @@ __global__ __launch_bounds__(kBlock) void fq_flat(const float* __restrict__ x, i
                                                   uint8_t* __restrict__ packed) {
   const QConst c = make_qconst(absmax[0], bits);
   const int64_t tid = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  const int64_t nthr = (int64_t)gridDim.x * kBlock;
-  const float4* x4 = reinterpret_cast<const float4*>(x);
   const int64_t n4 = n >> 2;
-  int64_t i = tid;
-  for (; i + 3 * nthr < n4; i += 4 * nthr) {
-    const float4 a = x4[i], b = x4[i + nthr], d = x4[i + 2 * nthr], e = x4[i + 3 * nthr];
-    emit4(a, c, i, y, codes, packed);
-    emit4(b, c, i + nthr, y, codes, packed);
-    emit4(d, c, i + 2 * nthr, y, codes, packed);
-    emit4(e, c, i + 3 * nthr, y, codes, packed);
-  }
-  for (; i < n4; i += nthr) emit4(x4[i], c, i, y, codes, packed);
+  for_each_vec4_tiled(reinterpret_cast<const float4*>(x), n4,
+                      [&](const float4 v, int64_t i) { emit4(v, c, i, y, codes, packed); });
   // tail: at most 3 elements, pairs stay together (n even whenever packed != null)
   if (tid == 0) {
     for (int64_t j = n4 << 2; j < n; ++j) {
@@ -171,7 +162,7 @@ extern "C" int mpq_fake_quant(const float* x, int64_t rows, int64_t cols, int gr
                       (!codes_out || (reinterpret_cast<uintptr_t>(codes_out) & 3u) == 0) &&
                       (!packed4_out || (reinterpret_cast<uintptr_t>(packed4_out) & 1u) == 0);
   if (vec_ok && gran == MPQ_PER_TENSOR) {
-    fq_flat<<<flat_grid(n >> 2, 4), kBlock, 0, st>>>(x, n, absmax, bits, y_out, codes_out, packed4_out);
+    fq_flat<<<flat_grid(n >> 2, kBlock * kTileVec), kBlock, 0, st>>>(x, n, absmax, bits, y_out, codes_out, packed4_out);
   } else if (vec_ok && gran == MPQ_PER_ROW && (cols & 3) == 0) {
     const int64_t nseg = (cols + kSeg - 1) / kSeg;
     const int64_t blocks = (rows * nseg + kBlock / kWave - 1) / (kBlock / kWave);
@@ -187,7 +178,7 @@ extern "C" int mpq_fake_quant(const float* x, int64_t rows, int64_t cols, int gr
     if (gy > 65535) gy = 65535;
     fq_cols<<<dim3((unsigned)gx, (unsigned)gy), kBlock, 0, st>>>(x, rows, cols, absmax, bits, y_out, codes_out, packed4_out);
   } else {
-    fq_generic<<<flat_grid((n + 1) >> 1, 4), kBlock, 0, st>>>(x, rows, cols, gran, absmax, bits, y_out, codes_out, packed4_out);
+    fq_generic<<<flat_grid((n + 1) >> 1, kBlock * 4), kBlock, 0, st>>>(x, rows, cols, gran, absmax, bits, y_out, codes_out, packed4_out);
   }
   return launch_status();
 }

@@ -118,13 +118,12 @@ __global__ __launch_bounds__(kBlock) void noise_vec(const float* __restrict__ x,
                                                     int bits, float lambda, unsigned long long seed,
                                                     unsigned long long sid, float* __restrict__ y) {
   const float sig0 = ROWS ? 0.0f : sigma_of(absmax[0], bits, lambda);
-  for (int64_t g = (int64_t)blockIdx.x * kBlock + threadIdx.x; g < n4; g += (int64_t)gridDim.x * kBlock) {
+  for_each_vec4_tiled(reinterpret_cast<const float4*>(x), n4, [&](const float4 v, int64_t g) {
     const float sig = ROWS ? sigma_of(absmax[g / cols4], bits, lambda) : sig0;
-    const float4 v = reinterpret_cast<const float4*>(x)[g];
     const float4 z = gauss4(seed, sid, (unsigned long long)g);
     reinterpret_cast<float4*>(y)[g] = make_float4(__builtin_fmaf(sig, z.x, v.x), __builtin_fmaf(sig, z.y, v.y),
                                                   __builtin_fmaf(sig, z.z, v.z), __builtin_fmaf(sig, z.w, v.w));
-  }
+  });
 }
 
 // ---- generic: any shape, alignment, granularity; a lane still owns one group of four ----------
@@ -165,11 +164,11 @@ extern "C" int mpq_noise_inject(const float* x, int64_t rows, int64_t cols, int 
   const int64_t n = rows * cols;
   const bool vec = aligned16(x) && aligned16(y_out) && (n & 3) == 0;
   if (vec && gran == MPQ_PER_TENSOR) {
-    noise_vec<false><<<flat_grid(n >> 2, 1), kBlock, 0, st>>>(x, n >> 2, 0, absmax, bits, lambda, seed, stream_id, y_out);
+    noise_vec<false><<<flat_grid(n >> 2, kBlock * kTileVec), kBlock, 0, st>>>(x, n >> 2, 0, absmax, bits, lambda, seed, stream_id, y_out);
   } else if (vec && gran == MPQ_PER_ROW && (cols & 3) == 0) {
-    noise_vec<true><<<flat_grid(n >> 2, 1), kBlock, 0, st>>>(x, n >> 2, cols >> 2, absmax, bits, lambda, seed, stream_id, y_out);
+    noise_vec<true><<<flat_grid(n >> 2, kBlock * kTileVec), kBlock, 0, st>>>(x, n >> 2, cols >> 2, absmax, bits, lambda, seed, stream_id, y_out);
   } else {
-    noise_generic<<<flat_grid((n + 3) >> 2, 1), kBlock, 0, st>>>(x, rows, cols, gran, absmax, bits, lambda, seed, stream_id, y_out);
+    noise_generic<<<flat_grid((n + 3) >> 2, kBlock * 2), kBlock, 0, st>>>(x, rows, cols, gran, absmax, bits, lambda, seed, stream_id, y_out);
   }
   return launch_status();
 }

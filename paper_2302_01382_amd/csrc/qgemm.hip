@@ -3,12 +3,16 @@
 // then Y = (float(acc) * s_A) * s_W[n].
 //
 // Both operands are K-contiguous, which is exactly what v_mfma_i32_32x32x32_i8 wants: lane l of
-// the A operand holds 16 consecutive k-bytes of row l%32 (k-half l/32), lane l of the B operand
-// the same for output column l%32.  Tiles go global -> registers -> LDS (16-byte chunks, XOR
-// swizzled by row so the 128-bit operand reads are bank-conflict free) -> MFMA.
+// either operand holds 16 consecutive k-bytes of tile row l%32 (k-half l/32).
 //
-// Packed int4 weights are expanded while staging: a nibble n becomes the byte n << 4 (= 16 n as
-// int8, sign included), so the accumulator holds 16 * acc exactly and is shifted back by 4.
+// Two kernels: the fast path (second half of this file; 16-byte aligned operands, K a multiple of
+// 16, or 32 for packed int4) feeds a multi-stage LDS pipeline with direct global->LDS loads; the
+// generic path right below stages tiles through registers with byte-wise loads and handles any
+// K and alignment.  Same arithmetic, same results.
+//
+// Packed int4 weights are expanded on their way to the matrix core: a nibble n becomes the byte
+// n << 4 (= 16 n as int8, sign included), so the accumulator holds 16 * acc exactly and is shifted
+// back by 4.
 #include "common.hpp"
 
 namespace mpq {
@@ -19,8 +23,9 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 constexpr int BM = 128, BN = 128, BK = 64;  // block tile; BK in bytes of k
 constexpr int kGemmThreads = 256;           // 4 waves as 2 x 2, each 64 x 64 = 2 x 2 MFMA tiles
 
-// byte offset of 16-byte chunk `ch` (0..3) of tile row `row` in a [rows][64 B] LDS tile
-__device__ __forceinline__ int lds_off(int row, int ch) { return row * BK + ((ch ^ ((row >> 1) & 3)) << 4); }
+// byte offset of 16-byte chunk `ch` (0..3) of tile row `row` in a [rows][64 B] LDS tile; the XOR makes
+// the 16 lanes served per clock (one chunk column of 16 rows) distinct modulo 256 B (64 banks)
+__device__ __forceinline__ int lds_off(int row, int ch) { return row * BK + ((ch ^ ((row >> 2) & 3)) << 4); }
 
 // 8 nibbles of `w` (lowest nibble = lowest k) -> 8 bytes, each nibble << 4, in k order
 __device__ __forceinline__ void expand8(unsigned w, unsigned& lo, unsigned& hi) {
@@ -182,6 +187,283 @@ __global__ __launch_bounds__(kGemmThreads) void qgemm_k(const int8_t* __restrict
   }
 }
 
+
+// =====================================================================================================
+// Fast path: multi-stage LDS pipeline fed by direct global->LDS loads (no register staging).
+//
+// k is walked in tiles of 128 bytes.  One wave-wide global_load_lds_dwordx4 moves 64 x 16 B = 1 KiB
+// and the hardware puts lane l's 16 bytes at LDS base + 16 l, so an instruction fills 8 whole tile
+// rows (16 rows of a packed-int4 tile).  To get a bank-conflict-free layout anyway, the *global*
+// chunk a lane fetches is permuted: LDS slot s of row r holds logical chunk s ^ ((r >> 1) & 7)
+// (int8 tiles, 8 chunks per row) or s ^ ((r >> 2) & 3) (packed tiles, 4 chunks per row).  The LDS
+// of gfx950 has 64 banks (256 B per clock, measured): a 128-bit operand read is served 16 lanes
+// per clock, those lanes read one chunk column of 16 consecutive rows, and with this XOR their
+// 16 addresses are distinct modulo 256 B.  The MFMA operand reads apply the same XOR.  Chunks
+// beyond K are fetched from a 16-byte block of zeros.
+//
+// Stage s + NSTAGE - 1 is requested right after the barrier that opens stage s, so loads run
+// NSTAGE - 1 tiles ahead of the MFMAs; a wave waits only for its own oldest tile (s_waitcnt vmcnt)
+// and then meets the others at the barrier.  The k loop is unrolled by NSTAGE so every LDS
+// address is a compile-time offset (the compiler then keeps ds_reads of one stage independent of
+// the loads in flight into the others).
+// =====================================================================================================
+#define MPQ_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
+#define MPQ_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
+
+__device__ __attribute__((aligned(16))) int g_zero16[4];  // never written: zero fill for k tails
+
+constexpr int DBK = 128;  // k bytes per stage
+
+// The direct-to-LDS load and its wait are written as inline assembly on purpose: when the
+// compiler sees the load it cannot tell which LDS bytes are in flight once more than a handful of
+// them are outstanding, and puts a full "s_waitcnt vmcnt(0)" in front of every LDS read -- which
+// would serialise the pipeline.  Written this way the compiler does not track them, and the
+// kernel does the bookkeeping itself: loads return in order, so "vmcnt(n)" means all but the
+// youngest n wave-loads of this wave have landed.
+// lds_byte_off must be wave-uniform (it travels in M0); lane l's 16 bytes land at +16 l.
+__device__ __forceinline__ void dma16(const char* src, unsigned lds_byte_off) {
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_byte_off) : "memory");
+}
+template <int N_>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N_) : "memory");
+}
+
+template <int BM, int BN, int WM, int WN, int NSTAGE, bool W4>
+struct DmaCfg {
+  static constexpr int NW = WM * WN;
+  static constexpr int NT = NW * 64;
+  static constexpr int TM = BM / WM, TN = BN / WN;   // per-wave tile
+  static constexpr int FM = TM / 32, FN = TN / 32;   // 32x32 MFMA tiles per wave
+  static constexpr int A_STAGE = BM * DBK;
+  static constexpr int B_ROW = W4 ? DBK / 2 : DBK;   // bytes of one W tile row in LDS
+  static constexpr int B_STAGE = BN * B_ROW;
+  static constexpr int STAGE = A_STAGE + B_STAGE;
+  static constexpr int LDS_BYTES = NSTAGE * STAGE;
+  static constexpr int NLA = BM / 8;                  // wave-loads per A stage (8 rows each)
+  static constexpr int NLB = W4 ? BN / 16 : BN / 8;   // wave-loads per W stage
+  static constexpr int LPW = (NLA + NLB) / NW;        // wave-loads per wave per stage
+  static_assert(NLA % NW == 0 && NLB % NW == 0, "loads must divide evenly over the waves");
+  static_assert(TM % 32 == 0 && TN % 32 == 0, "wave tile is a multiple of 32 x 32");
+  static_assert((NSTAGE - 1) * LPW < 64, "vmcnt is a 6-bit counter");
+};
+
+// lds_stage_off: LDS byte offset of the stage (wave-uniform); wave_u: wave id in an SGPR
+template <class C, bool W4>
+__device__ __forceinline__ void dma_issue_stage(unsigned lds_stage_off, const int8_t* __restrict__ A,
+                                                const uint8_t* __restrict__ W, int64_t M, int64_t N,
+                                                int64_t K, int64_t m0, int64_t n0, int64_t k0,
+                                                int wave_u, int lane) {
+  const char* zero = reinterpret_cast<const char*>(g_zero16);
+  {  // A tile: wave-load j covers rows 8j .. 8j+7
+    const int lr = lane >> 3;          // row within the 8-row group
+#pragma unroll
+    for (int t = 0; t < C::NLA / C::NW; ++t) {
+      const int j = wave_u + t * C::NW;
+      const int c = (lane & 7) ^ (((8 * j + lr) >> 1) & 7);  // logical chunk this lane fetches
+      const int64_t kk = k0 + c * 16;
+      const bool live = kk < K;
+      int64_t r = m0 + 8 * j + lr;
+      if (r >= M) r = M - 1;
+      const char* src = live ? reinterpret_cast<const char*>(A) + r * K + kk : zero;
+      dma16(src, lds_stage_off + (unsigned)j * 1024u);
+    }
+  }
+  if (!W4) {
+    const int lr = lane >> 3;
+#pragma unroll
+    for (int t = 0; t < C::NLB / C::NW; ++t) {
+      const int j = wave_u + t * C::NW;
+      const int c = (lane & 7) ^ (((8 * j + lr) >> 1) & 7);
+      const int64_t kk = k0 + c * 16;
+      const bool live = kk < K;
+      int64_t r = n0 + 8 * j + lr;
+      if (r >= N) r = N - 1;
+      const char* src = live ? reinterpret_cast<const char*>(W) + r * K + kk : zero;
+      dma16(src, lds_stage_off + (unsigned)C::A_STAGE + (unsigned)j * 1024u);
+    }
+  } else {  // packed tile: wave-load j covers rows 16j .. 16j+15 of 64 packed bytes
+    const int lr = lane >> 2;
+    const int c = (lane & 3) ^ ((lr >> 2) & 3);   // logical 16-byte chunk = 32 values (16 j + lr: same bits)
+    const int64_t kk = k0 + c * 32;               // first k of the chunk
+    const bool live = kk < K;
+#pragma unroll
+    for (int t = 0; t < C::NLB / C::NW; ++t) {
+      const int j = wave_u + t * C::NW;
+      int64_t r = n0 + 16 * j + lr;
+      if (r >= N) r = N - 1;
+      const char* src = live ? reinterpret_cast<const char*>(W) + r * (K >> 1) + (kk >> 1) : zero;
+      dma16(src, lds_stage_off + (unsigned)C::A_STAGE + (unsigned)j * 1024u);
+    }
+  }
+}
+
+// operand fragments of k-substep s (32 k-values) of one stage
+template <class C, bool W4>
+__device__ __forceinline__ void dma_load_frags(const char* lds_stage, int s, int wm, int wn, int lane,
+                                               v4i (&fa)[C::FM], v4i (&fb)[C::FN]) {
+  const int l31 = lane & 31, g = lane >> 5;
+  const int ch = 2 * s + g;  // logical 16-byte chunk of the 128-byte row
+#pragma unroll
+  for (int i = 0; i < C::FM; ++i) {
+    const int row = wm * C::TM + i * 32 + l31;
+    fa[i] = *reinterpret_cast<const v4i*>(lds_stage + row * DBK + ((ch ^ ((row >> 1) & 7)) << 4));
+  }
+#pragma unroll
+  for (int j = 0; j < C::FN; ++j) {
+    const int row = wn * C::TN + j * 32 + l31;
+    if (!W4) {
+      fb[j] = *reinterpret_cast<const v4i*>(lds_stage + C::A_STAGE + row * DBK + ((ch ^ ((row >> 1) & 7)) << 4));
+    } else {
+      // 16 values = 8 packed bytes: half g of logical packed chunk s
+      const uint2 pk = *reinterpret_cast<const uint2*>(lds_stage + C::A_STAGE + row * (DBK / 2) +
+                                                       ((s ^ ((row >> 2) & 3)) << 4) + g * 8);
+      unsigned b0, b1, b2, b3;
+      expand8(pk.x, b0, b1);
+      expand8(pk.y, b2, b3);
+      fb[j] = v4i{(int)b0, (int)b1, (int)b2, (int)b3};
+    }
+  }
+}
+
+// all MFMAs of one stage; the fragments of substep s+1 are requested before the MFMAs of substep s
+// are issued, so the LDS latency hides behind the matrix pipe
+template <class C, bool W4>
+__device__ __forceinline__ void dma_compute_stage(const char* lds_stage, v16i (&acc)[C::FM][C::FN],
+                                                  int wm, int wn, int lane) {
+  constexpr int NSUB = DBK / 32;
+  v4i fa[2][C::FM], fb[2][C::FN];
+  dma_load_frags<C, W4>(lds_stage, 0, wm, wn, lane, fa[0], fb[0]);
+#pragma unroll
+  for (int s = 0; s < NSUB; ++s) {
+    if (s + 1 < NSUB) dma_load_frags<C, W4>(lds_stage, s + 1, wm, wn, lane, fa[(s + 1) & 1], fb[(s + 1) & 1]);
+#pragma unroll
+    for (int i = 0; i < C::FM; ++i)
+#pragma unroll
+      for (int j = 0; j < C::FN; ++j)
+        // W fragment as the row operand: the lane then holds 4 consecutive n per register
+        // group, which the epilogue stores as one 16-byte piece of a Y row
+        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[s & 1][j], fa[s & 1][i], acc[i][j], 0, 0, 0);
+  }
+}
+
+// grid: 1-D over output tiles, N fastest; `swizzle_xcd` regroups block ids so that the blocks an
+// XCD receives (ids congruent mod 8) cover one contiguous range of tiles and share its L2.
+template <int BM, int BN, int WM, int WN, int NSTAGE, bool W4, bool VEC>
+__global__ __launch_bounds__(WM * WN * 64) void qgemm_dma(const int8_t* __restrict__ A,
+                                                          const void* __restrict__ Wv, int64_t M,
+                                                          int64_t N, int64_t K,
+                                                          const float* __restrict__ a_scale,
+                                                          const float* __restrict__ w_scale,
+                                                          int w_per_row, float* __restrict__ Y,
+                                                          int32_t* __restrict__ ACC, int tiles_n,
+                                                          int swizzle_xcd) {
+  using C = DmaCfg<BM, BN, WM, WN, NSTAGE, W4>;
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int wm = wave / WN, wn = wave % WN;
+  const unsigned lds0 = (unsigned)(uintptr_t)MPQ_LPTR(lds);  // LDS byte address of the buffer
+  unsigned bid = blockIdx.x;
+  if (swizzle_xcd) bid = (bid & 7u) * (gridDim.x >> 3) + (bid >> 3);  // gridDim.x % 8 == 0
+  const int64_t m0 = (int64_t)(bid / (unsigned)tiles_n) * BM, n0 = (int64_t)(bid % (unsigned)tiles_n) * BN;
+  const uint8_t* Wb = reinterpret_cast<const uint8_t*>(Wv);
+
+  v16i acc[C::FM][C::FN];
+#pragma unroll
+  for (int i = 0; i < C::FM; ++i)
+#pragma unroll
+    for (int j = 0; j < C::FN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+
+  const int KT = (int)((K + DBK - 1) / DBK);
+  // prologue: tiles 0 .. NSTAGE-2 (tiles past the end fetch zeros: harmless and keeps vmcnt uniform)
+#pragma unroll
+  for (int p = 0; p < NSTAGE - 1; ++p)
+    dma_issue_stage<C, W4>(lds0 + p * C::STAGE, A, Wb, M, N, K, m0, n0, (int64_t)p * DBK, wave, lane);
+
+  for (int kt = 0; kt < KT; kt += NSTAGE) {
+#pragma unroll
+    for (int u = 0; u < NSTAGE; ++u) {
+      if (kt + u < KT) {  // block-uniform
+        wait_vmcnt<(NSTAGE - 2) * C::LPW>();  // this wave's share of tile kt+u has landed
+        __syncthreads();                    // everyone's share has landed; stage (u-1) is free again
+        dma_issue_stage<C, W4>(lds0 + ((u + NSTAGE - 1) % NSTAGE) * C::STAGE, A, Wb, M, N, K, m0, n0,
+                               (int64_t)(kt + u + NSTAGE - 1) * DBK, wave, lane);
+        dma_compute_stage<C, W4>(lds + u * C::STAGE, acc, wm, wn, lane);
+      }
+    }
+  }
+  wait_vmcnt<0>();  // drain the zero-fill tail loads before the block retires
+
+  // epilogue.  32x32 accumulator tile (i, j): lane l holds m = l % 32 and, in registers
+  // 4g .. 4g+3, the four consecutive n = 8g + 4 (l / 32) + 0..3.
+  const float sa = Y ? a_scale[0] : 0.0f;
+  const float sw0 = (Y && !w_per_row) ? w_scale[0] : 0.0f;
+#pragma unroll
+  for (int i = 0; i < C::FM; ++i) {
+    const int64_t m = m0 + wm * C::TM + i * 32 + (lane & 31);
+    if (m >= M) continue;
+#pragma unroll
+    for (int j = 0; j < C::FN; ++j) {
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const int64_t n = n0 + wn * C::TN + j * 32 + g4 * 8 + (lane >> 5) * 4;
+        if (n >= N) continue;
+        int a[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          a[e] = acc[i][j][g4 * 4 + e];
+          if (W4) a[e] >>= 4;  // exact: every product carried the factor 16
+        }
+        if (VEC) {  // N % 4 == 0 and 16-byte aligned outputs: the four n are all in range
+          if (ACC) *reinterpret_cast<v4i*>(ACC + m * N + n) = v4i{a[0], a[1], a[2], a[3]};
+          if (Y) {
+            float4 sw = make_float4(sw0, sw0, sw0, sw0);
+            if (w_per_row) sw = *reinterpret_cast<const float4*>(w_scale + n);
+            *reinterpret_cast<float4*>(Y + m * N + n) =
+                make_float4(((float)a[0] * sa) * sw.x, ((float)a[1] * sa) * sw.y,
+                            ((float)a[2] * sa) * sw.z, ((float)a[3] * sa) * sw.w);
+          }
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            if (n + e >= N) break;
+            if (ACC) ACC[m * N + n + e] = a[e];
+            if (Y) Y[m * N + n + e] = ((float)a[e] * sa) * (w_per_row ? w_scale[n + e] : sw0);
+          }
+        }
+      }
+    }
+  }
+}
+
+template <int BM, int BN, int WM, int WN, int NSTAGE, bool W4>
+static int launch_dma(const int8_t* a_q, const void* w_q, int64_t M, int64_t N, int64_t K,
+                      const float* a_scale, const float* w_scale, int per_row, float* y_out,
+                      int32_t* acc_out, hipStream_t st) {
+  using C = DmaCfg<BM, BN, WM, WN, NSTAGE, W4>;
+  // float4 / int4 stores need every 4-group of n inside the row and 16-byte aligned
+  const bool vec = (N & 3) == 0 && (!y_out || aligned16(y_out)) && (!acc_out || aligned16(acc_out)) &&
+                   (!(y_out && per_row) || aligned16(w_scale));
+  auto kern = vec ? qgemm_dma<BM, BN, WM, WN, NSTAGE, W4, true> : qgemm_dma<BM, BN, WM, WN, NSTAGE, W4, false>;
+  static bool attr_set[2] = {false, false};  // dynamic LDS above 64 KiB has to be allowed once per kernel
+  if (!attr_set[vec]) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+    if (e != hipSuccess) { set_last_hip_error((int)e); return MPQ_ERR_HIP; }
+    attr_set[vec] = true;
+  }
+  const int64_t tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN;
+  if (tm * tn > 0x7FFFFFFF || tn > 0x7FFFFFFF) return MPQ_ERR_SHAPE;
+  const unsigned grid = (unsigned)(tm * tn);
+  const int swz = (grid % 8u == 0 && grid >= 16u) ? 1 : 0;
+  kern<<<grid, C::NT, C::LDS_BYTES, st>>>(a_q, w_q, M, N, K, a_scale, w_scale, per_row, y_out, acc_out,
+                                          (int)tn, swz);
+  return launch_status();
+}
+
 }  // namespace mpq
 
 using namespace mpq;
@@ -214,6 +496,23 @@ extern "C" int mpq_qgemm(const int8_t* a_q, const void* w_q, int w_storage_bits,
   const bool fast = aligned16(a_q) && aligned16(w_q) && (K % (w4 ? 32 : 16)) == 0;
 #define MPQ_LAUNCH(W4_, FAST_) \
   qgemm_k<W4_, FAST_><<<grid, kGemmThreads, 0, st>>>(a_q, w_q, M, N, K, a_scale, w_scale, per_row, y_out, acc_out)
+  if (fast) {
+    // tile choice: the largest tile that still gives every CU a block (tiles >= number of CUs)
+    // and does not pad N by more than its own width; small problems take the 64 x 64 tile.
+    auto tiles = [&](int64_t bm, int64_t bn) { return ((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
+    int pick = 64;
+    if (N > 128 && tiles(256, 256) >= kNumCU) pick = 256;
+    else if (N > 64 && tiles(128, 128) >= kNumCU) pick = 128;
+#define MPQ_DMA(BM_, BN_, WM_, WN_, NS_)                                                              \
+  (w4 ? launch_dma<BM_, BN_, WM_, WN_, NS_, true>(a_q, w_q, M, N, K, a_scale, w_scale, per_row, y_out, \
+                                                  acc_out, st)                                        \
+      : launch_dma<BM_, BN_, WM_, WN_, NS_, false>(a_q, w_q, M, N, K, a_scale, w_scale, per_row,     \
+                                                   y_out, acc_out, st))
+    if (pick == 256) return MPQ_DMA(256, 256, 4, 2, 2);
+    if (pick == 128) return MPQ_DMA(128, 128, 4, 2, 2);
+    return MPQ_DMA(64, 64, 2, 2, 2);
+#undef MPQ_DMA
+  }
   if (w4) { if (fast) MPQ_LAUNCH(true, true); else MPQ_LAUNCH(true, false); }
   else { if (fast) MPQ_LAUNCH(false, true); else MPQ_LAUNCH(false, false); }
 #undef MPQ_LAUNCH

@@ -54,14 +54,8 @@ __global__ __launch_bounds__(kBlock) void qe_flat(const float* __restrict__ x, i
   const int64_t tid = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   const int64_t nthr = (int64_t)gridDim.x * kBlock;
   if (VEC) {
-    const float4* x4 = reinterpret_cast<const float4*>(x);
     const int64_t n4 = n >> 2;
-    int64_t i = tid;
-    for (; i + 3 * nthr < n4; i += 4 * nthr) {
-      const float4 a = x4[i], b = x4[i + nthr], c = x4[i + 2 * nthr], d = x4[i + 3 * nthr];
-      s.add4(a); s.add4(b); s.add4(c); s.add4(d);
-    }
-    for (; i < n4; i += nthr) s.add4(x4[i]);
+    for_each_vec4_tiled(reinterpret_cast<const float4*>(x), n4, [&](const float4 v, int64_t) { s.add4(v); });
     for (int64_t j = (n4 << 2) + tid; j < n; j += nthr) s.add(x[j]);
   } else {
     for (int64_t j = tid; j < n; j += nthr) s.add(x[j]);
@@ -80,24 +74,31 @@ __global__ __launch_bounds__(kBlock) void qe_flat(const float* __restrict__ x, i
         ((double)sm[2][threadIdx.x] + (double)sm[3][threadIdx.x]);
 }
 
-// out[ch][b] = sum_p partials[ch][p][b], p < np, in a fixed order.  One block per channel when
-// np is large (tree = true), else one thread per (channel, b).
+// out[b] = sum_p partials[p][b], p < np, in a fixed order: thread t adds p = t, t + 256, ...
+// (independent loads, unrolled), then a fixed LDS tree over the 256 threads.
+template <int NB>
 __global__ __launch_bounds__(kBlock) void qe_finish_tree(const double* __restrict__ partials,
-                                                         int64_t np, int nb, double* __restrict__ out) {
-  // 32 groups x 8 slots; group g sums p = g, g+32, ...; then a fixed tree over groups
-  const int slot = threadIdx.x & 7, g = threadIdx.x >> 3;
-  const double* base = partials + (int64_t)blockIdx.x * np * nb;
-  double a = 0.0;
-  if (slot < nb)
-    for (int64_t p = g; p < np; p += 32) a += base[p * nb + slot];
-  __shared__ double sm[32][8];
-  sm[g][slot] = a;
+                                                         int64_t np, double* __restrict__ out) {
+  double a[NB];
+#pragma unroll
+  for (int b = 0; b < NB; ++b) a[b] = 0.0;
+#pragma unroll 4
+  for (int64_t p = threadIdx.x; p < np; p += kBlock) {
+#pragma unroll
+    for (int b = 0; b < NB; ++b) a[b] += partials[p * NB + b];
+  }
+  __shared__ double sm[kBlock][NB];
+#pragma unroll
+  for (int b = 0; b < NB; ++b) sm[threadIdx.x][b] = a[b];
   __syncthreads();
-  for (int half = 16; half >= 1; half >>= 1) {
-    if (g < half) sm[g][slot] += sm[g + half][slot];
+  for (int half = kBlock / 2; half >= 1; half >>= 1) {
+    if ((int)threadIdx.x < half) {
+#pragma unroll
+      for (int b = 0; b < NB; ++b) sm[threadIdx.x][b] += sm[threadIdx.x + half][b];
+    }
     __syncthreads();
   }
-  if (g == 0 && slot < nb) out[(int64_t)blockIdx.x * nb + slot] = sm[0][slot];
+  if (threadIdx.x < NB) out[threadIdx.x] = sm[0][threadIdx.x];
 }
 
 // partials laid out [np][nch][nb] (per-column kernels) or [nch][np][nb] (per-row kernels)
@@ -201,19 +202,11 @@ __global__ __launch_bounds__(kBlock) void sse_pair_k(const float* __restrict__ y
   float acc = 0.0f;
   auto add = [&](float a, float b) { const float e = a - b; acc = __builtin_fmaf(e, e, acc); };
   if (VEC) {
-    const float4* a4 = reinterpret_cast<const float4*>(y);
-    const float4* b4 = reinterpret_cast<const float4*>(yr);
     const int64_t n4 = n >> 2;
-    int64_t i = tid;
-    for (; i + nthr < n4; i += 2 * nthr) {
-      const float4 a0 = a4[i], b0 = b4[i], a1 = a4[i + nthr], b1 = b4[i + nthr];
-      add(a0.x, b0.x); add(a0.y, b0.y); add(a0.z, b0.z); add(a0.w, b0.w);
-      add(a1.x, b1.x); add(a1.y, b1.y); add(a1.z, b1.z); add(a1.w, b1.w);
-    }
-    for (; i < n4; i += nthr) {
-      const float4 a0 = a4[i], b0 = b4[i];
-      add(a0.x, b0.x); add(a0.y, b0.y); add(a0.z, b0.z); add(a0.w, b0.w);
-    }
+    for_each_vec4_pair_tiled(reinterpret_cast<const float4*>(y), reinterpret_cast<const float4*>(yr), n4,
+                             [&](const float4 a, const float4 b) {
+                               add(a.x, b.x); add(a.y, b.y); add(a.z, b.z); add(a.w, b.w);
+                             });
     for (int64_t j = (n4 << 2) + tid; j < n; j += nthr) add(y[j], yr[j]);
   } else {
     for (int64_t j = tid; j < n; j += nthr) add(y[j], yr[j]);
@@ -239,9 +232,12 @@ static QeGeom qe_geometry(int64_t rows, int64_t cols, int gran, int nb, bool ali
   const int64_t n = rows * cols;
   if (gran == MPQ_PER_TENSOR) {
     g.vec = aligned;
-    g.gx = g.vec ? flat_grid(n >> 2, 4) : flat_grid(n, 4);
+    // 4 blocks per CU: the full sweep needs ~65 VGPRs (7 waves per SIMD), so 8 blocks per CU
+    // would not be co-resident and the late blocks would trail the rest
+    const unsigned gv = flat_grid(n >> 2, kBlock * kTileVec, 4), gs = flat_grid(n, kBlock * 4, 4);
+    g.gx = g.vec ? gv : gs;
     // the query cannot see the pointer: reserve for the larger of the two grids
-    const unsigned worst = flat_grid(n, 4) > flat_grid(n >> 2, 4) ? flat_grid(n, 4) : flat_grid(n >> 2, 4);
+    const unsigned worst = gv > gs ? gv : gs;
     g.partial_doubles = (int64_t)worst * nb;
   } else if (gran == MPQ_PER_ROW) {
     g.vec = aligned && (cols & 3) == 0;
@@ -278,7 +274,7 @@ static void launch_qe(const QeGeom& g, const float* x, int64_t rows, int64_t col
   if (gran == MPQ_PER_TENSOR) {
     if (g.vec) qe_flat<NB, true><<<g.gx, kBlock, 0, st>>>(x, n, absmax, b_lo, ws);
     else qe_flat<NB, false><<<g.gx, kBlock, 0, st>>>(x, n, absmax, b_lo, ws);
-    qe_finish_tree<<<1, kBlock, 0, st>>>(ws, (int64_t)g.gx, NB, out);
+    qe_finish_tree<NB><<<1, kBlock, 0, st>>>(ws, (int64_t)g.gx, out);
   } else if (gran == MPQ_PER_ROW) {
     double* dst = g.nseg == 1 ? out : ws;
     if (g.vec) qe_rows<NB, true><<<g.gx, kBlock, 0, st>>>(x, rows, cols, g.nseg, absmax, b_lo, dst);
@@ -344,7 +340,7 @@ extern "C" int mpq_quant_error(const float* x, int64_t rows, int64_t cols, int g
 
 extern "C" size_t mpq_sse_pair_workspace_bytes(int64_t n) {
   if (n <= 0 || n > ((int64_t)1 << 46)) return 0;
-  const unsigned a = flat_grid(n >> 2, 4), b = flat_grid(n, 4);
+  const unsigned a = flat_grid(n >> 2, kBlock * 2), b = flat_grid(n, kBlock * 4);
   return (size_t)(a > b ? a : b) * sizeof(double);
 }
 
@@ -353,13 +349,13 @@ extern "C" int mpq_sse_pair(const float* y, const float* y_ref, int64_t n, doubl
   if (!y || !y_ref || !sse_out) return MPQ_ERR_NULL;
   if (n <= 0 || n > ((int64_t)1 << 46)) return MPQ_ERR_SHAPE;
   const bool vec = aligned16(y) && aligned16(y_ref);
-  const unsigned grid = vec ? flat_grid(n >> 2, 4) : flat_grid(n, 4);
+  const unsigned grid = vec ? flat_grid(n >> 2, kBlock * 2) : flat_grid(n, kBlock * 4);
   if (!ws || ws_bytes < mpq_sse_pair_workspace_bytes(n)) return MPQ_ERR_WORKSPACE;
   if (!aligned16(ws) || (reinterpret_cast<uintptr_t>(sse_out) & 7u) != 0) return MPQ_ERR_ALIGN;
   hipStream_t st = (hipStream_t)stream;
   double* wsd = reinterpret_cast<double*>(ws);
   if (vec) sse_pair_k<true><<<grid, kBlock, 0, st>>>(y, y_ref, n, wsd);
   else sse_pair_k<false><<<grid, kBlock, 0, st>>>(y, y_ref, n, wsd);
-  qe_finish_tree<<<1, kBlock, 0, st>>>(wsd, (int64_t)grid, 1, sse_out);
+  qe_finish_tree<1><<<1, kBlock, 0, st>>>(wsd, (int64_t)grid, sse_out);
   return launch_status();
 }

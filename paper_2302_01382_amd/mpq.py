@@ -17,7 +17,8 @@ OK = 0
 ERR_NULL, ERR_SHAPE, ERR_BITS, ERR_ALIGN, ERR_WORKSPACE, ERR_GRAN, ERR_HIP = 1, 2, 3, 4, 5, 6, 7
 
 EXPORTS = [
-    "mpq_strerror", "mpq_last_hip_error", "mpq_version", "mpq_calibrate_absmax",
+    "mpq_strerror", "mpq_last_hip_error", "mpq_version", "mpq_calibrate_absmax_workspace_bytes",
+    "mpq_calibrate_absmax",
     "mpq_scale_from_absmax", "mpq_fake_quant", "mpq_quant_error_workspace_bytes",
     "mpq_quant_error", "mpq_noise_inject", "mpq_qgemm_workspace_bytes", "mpq_qgemm",
     "mpq_sse_pair_workspace_bytes", "mpq_sse_pair",
@@ -48,7 +49,9 @@ def lib():
         L.mpq_strerror.argtypes = [ci]
         L.mpq_last_hip_error.restype = ci
         L.mpq_version.restype = ci
-        L.mpq_calibrate_absmax.argtypes = [vp, i64, i64, ci, ci, vp, vp]
+        L.mpq_calibrate_absmax_workspace_bytes.restype = sz
+        L.mpq_calibrate_absmax_workspace_bytes.argtypes = [i64, i64, ci]
+        L.mpq_calibrate_absmax.argtypes = [vp, i64, i64, ci, ci, vp, vp, sz, vp]
         L.mpq_scale_from_absmax.argtypes = [vp, i64, ci, vp, vp]
         L.mpq_fake_quant.argtypes = [vp, i64, i64, ci, vp, ci, vp, vp, vp, vp]
         L.mpq_quant_error_workspace_bytes.restype = sz
@@ -119,7 +122,11 @@ _default_ws = Workspace()
 
 
 # ---------------------------------------------------------------------------------------------
-def calibrate_absmax(x, gran=PER_TENSOR, out=None, accumulate=False):
+def calibrate_absmax_workspace_bytes(rows, cols, gran=PER_TENSOR) -> int:
+    return int(lib().mpq_calibrate_absmax_workspace_bytes(rows, cols, gran))
+
+
+def calibrate_absmax(x, gran=PER_TENSOR, out=None, accumulate=False, ws: "Workspace" = None):
     torch = _torch()
     x = _dev2d(x, torch.float32)
     rows, cols = x.shape
@@ -127,7 +134,8 @@ def calibrate_absmax(x, gran=PER_TENSOR, out=None, accumulate=False):
         if accumulate:
             raise ValueError("accumulate needs the running absmax in `out`")
         out = torch.empty(_nch(gran, rows, cols), dtype=torch.float32, device=x.device)
-    _check(lib().mpq_calibrate_absmax(_ptr(x), rows, cols, gran, int(accumulate), _ptr(out),
+    wp, wn = (ws or _default_ws).get(calibrate_absmax_workspace_bytes(rows, cols, gran))
+    _check(lib().mpq_calibrate_absmax(_ptr(x), rows, cols, gran, int(accumulate), _ptr(out), wp, wn,
                                       _stream()), "mpq_calibrate_absmax")
     return out
 

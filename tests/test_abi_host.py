@@ -33,7 +33,7 @@ def declared_functions():
 
 def test_library_exports_every_declared_symbol():
     names = declared_functions()
-    assert len(names) >= 13
+    assert len(names) >= 14
     L = mpq.lib()
     for n in names:
         assert hasattr(L, n), n
@@ -63,12 +63,17 @@ def test_strerror_and_version():
 def test_calibrate_absmax_validation():
     L = mpq.lib()
     f = L.mpq_calibrate_absmax
-    assert f(None, 4, 4, 0, 0, FAKE, None) == mpq.ERR_NULL
-    assert f(FAKE, 4, 4, 0, 0, None, None) == mpq.ERR_NULL
-    assert f(FAKE, 0, 4, 0, 0, FAKE, None) == mpq.ERR_SHAPE
-    assert f(FAKE, 4, -1, 0, 0, FAKE, None) == mpq.ERR_SHAPE
-    assert f(FAKE, 2 ** 40, 2 ** 40, 0, 0, FAKE, None) == mpq.ERR_SHAPE
-    assert f(FAKE, 4, 4, 3, 0, FAKE, None) == mpq.ERR_GRAN
+    q = L.mpq_calibrate_absmax_workspace_bytes
+    assert q(1000, 1000, 0) > 0 and q(1000, 1000, 1) == 0 and q(1000, 1000, 2) == 0 and q(0, 4, 0) == 0
+    assert f(None, 4, 4, 0, 0, FAKE, FAKE16, 1 << 20, None) == mpq.ERR_NULL
+    assert f(FAKE, 4, 4, 0, 0, None, FAKE16, 1 << 20, None) == mpq.ERR_NULL
+    assert f(FAKE, 0, 4, 0, 0, FAKE, FAKE16, 1 << 20, None) == mpq.ERR_SHAPE
+    assert f(FAKE, 4, -1, 0, 0, FAKE, FAKE16, 1 << 20, None) == mpq.ERR_SHAPE
+    assert f(FAKE, 2 ** 40, 2 ** 40, 0, 0, FAKE, FAKE16, 1 << 20, None) == mpq.ERR_SHAPE
+    assert f(FAKE, 4, 4, 3, 0, FAKE, FAKE16, 1 << 20, None) == mpq.ERR_GRAN
+    assert f(FAKE, 1000, 1000, 0, 0, FAKE, None, 0, None) == mpq.ERR_WORKSPACE
+    assert f(FAKE, 1000, 1000, 0, 0, FAKE, FAKE16, q(1000, 1000, 0) - 1, None) == mpq.ERR_WORKSPACE
+    assert f(FAKE, 1000, 1000, 0, 0, FAKE, C.c_void_p(0x10004), 1 << 20, None) == mpq.ERR_ALIGN
     assert L.mpq_scale_from_absmax(FAKE, 4, 9, FAKE, None) == mpq.ERR_BITS
     assert L.mpq_scale_from_absmax(FAKE, 0, 8, FAKE, None) == mpq.ERR_SHAPE
     assert L.mpq_scale_from_absmax(None, 4, 8, FAKE, None) == mpq.ERR_NULL

@@ -243,6 +243,30 @@ def test_qgemm_packed_int4_weights_bit_exact(mnk):
     np.testing.assert_array_equal(host(acc8), acc_o)
 
 
+@pytest.mark.parametrize("mnk,wbits", [((4096, 4096, 256), 8), ((4100, 4092, 160), 4), ((2048, 2048, 384), 8),
+                                        ((2085, 2047, 96), 4), ((2085, 2046, 112), 8), ((16384, 1024, 4096), 8)])
+def test_qgemm_large_tiles_on_sampled_rows(mnk, wbits):
+    """Shapes that select the 128 x 128 and 256 x 256 tiles (ragged edges, N not a multiple of 4);
+    rows of the product are independent, so the oracle checks a sample of rows exactly."""
+    M, N, K = mnk
+    q = 127 if wbits == 8 else 7
+    a, w = rand_codes((M, K), 127, 30), rand_codes((N, K), q, 31)
+    ws = w if wbits == 8 else oracle.pack4(w)
+    sa = np.array([0.02], np.float32)
+    sw = (np.random.Generator(np.random.PCG64(32)).random(N).astype(np.float32) + 0.5) * np.float32(1e-3)
+    y, acc = mpq.qgemm(dev(a), dev(ws), dev(sa), dev(sw), wbits, mpq.PER_ROW, want_y=True, want_acc=True)
+    r = np.random.Generator(np.random.PCG64(33))
+    rows = np.unique(np.concatenate([[0, 1, 31, 32, 63, 64, 127, 128, 255, 256, M - 257, M - 129, M - 2, M - 1],
+                                     r.integers(0, M, 40)]))
+    y_o, acc_o = oracle.qgemm(a[rows], ws, sa, sw, wbits, oracle.PER_ROW)
+    np.testing.assert_array_equal(host(acc)[rows], acc_o)
+    np.testing.assert_allclose(host(y)[rows], y_o, rtol=RTOL_Y, atol=0)
+    # every row against a wide-integer matmul on the device side of torch would be plumbing; a
+    # cheap global invariant instead: column sums of acc equal (sum of A rows) . W
+    colsum = a.astype(np.int64).sum(0) @ w.astype(np.int64).T
+    np.testing.assert_array_equal(host(acc).astype(np.int64).sum(0), colsum)
+
+
 def test_qgemm_extreme_operands_and_single_outputs():
     a = np.full((130, 4608), -127, np.int8)
     w = np.full((70, 4608), 127, np.int8)
