@@ -298,6 +298,22 @@ def test_sse_pair(n):
     assert host(mpq.sse_pair(dev(a), dev(a)))[0] == 0.0
 
 
+def test_workspace_needs_no_initialisation_and_is_reusable():
+    """One workspace serves call after call, whatever it holds on entry."""
+    ws = mpq.Workspace()
+    ws.get(1 << 20)
+    x = data((700, 1028), 40)
+    y = (x + 0.01).astype(np.float32)
+    dx, dy = dev(x), dev(y)
+    for fill in (0xFF, 0x00, 0xAB):
+        ws.buf[:] = fill
+        am = mpq.calibrate_absmax(dx, ws=ws)
+        np.testing.assert_array_equal(host(am), oracle.absmax(x))
+        np.testing.assert_allclose(host(mpq.quant_error(dx, am, ws=ws)), oracle.quant_error(x, oracle.absmax(x)),
+                                   rtol=RTOL_SSE)
+        assert host(mpq.sse_pair(dx, dy, ws=ws))[0] == pytest.approx(oracle.sse_pair(x, y), rel=RTOL_SSE)
+
+
 # ------------------------------------------------------------------ configuration 1 end to end
 def test_config1_whole_path():
     x, w = workloads.cfg1_tensors(0)
