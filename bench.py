@@ -2,14 +2,19 @@
 """Benchmark of the libmpq hot path on one MI355X.
 
 One "step" = one pass of the whole hot path over one batch of synthetic input of the chosen
-workload.  Default workload: configuration 2, the ResNet-50-shaped conv-as-GEMM stack (8 layers at
-batch 32).  Per layer a step runs, through the C ABI:
+workload.  Default workload (`--workload cfg2`): configuration 2, the ResNet-50-shaped
+conv-as-GEMM stack (8 layers at batch 32).  Per layer a step runs, through the C ABI:
     absmax(A) per tensor, absmax(W) per output channel            (calibration, Sec. 3.1)
     quant_error(A) and quant_error(W), b = 2..8 in one read each  (Eq. 2)
     noise_inject(W) at the layer's weight bit-width               (Eq. 3-5)
     fake_quant(A) -> int8 codes, fake_quant(W) -> int8 / packed int4 codes, the two step sizes
     qgemm -> fp32 Y                                               ("Evaluate f(x, w)")
     sse_pair(Y, Y_ref)                                            (candidate score)
+Other workloads (the parity-test configurations, measured with the same machinery):
+    cfg3  BERT-base encoder linears at M = 12288, same per-layer path, per-tensor scales
+    cfg4  sensitivity sweep over the 96 BERT-large weight tensors: absmax + quant_error per tensor
+          and per output channel, noise at every b = 2..8
+    cfg5  64 candidate bit configurations of a BERT-large FFN block at M = 16384, back to back
 All inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 """
 from __future__ import annotations
@@ -28,14 +33,14 @@ if ROOT not in sys.path:
 METRIC = "qgemm int8 TOPS (% MFMA peak); quant+error sweep GB/s (% HBM peak)"
 HBM_PEAK_GBS = 8000.0
 INT8_PEAK_TOPS = 5000.0
+ALU_PEAK_TLANEOPS = 256 * 64 * 2.4e9 / 1e12   # 256 CUs x 64 lanes x 2.4 GHz, no packed math
 LAMBDA = 0.28867513  # 1/sqrt(12): noise with the variance of uniform rounding error of one step
 
-CALLS = ["absmax", "quant_error", "noise_inject", "fake_quant", "qgemm", "sse_pair"]
-
-# HBM traffic per main-stream launch (activation tensor of a layer, averaged over the 8 layers),
-# in KiB, from the rocprofv3 counter runs summarised in profiles/cfg2_hot_path_hbm_traffic.txt:
-# FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 of the call's kernels (main + finishing kernel).
-TRAFFIC_KIB_PER_LAUNCH = {
+# HBM traffic per main-stream launch of configuration 2 (activation tensor of a layer, averaged
+# over the 8 layers), in KiB, from the rocprofv3 counter runs summarised in
+# profiles/cfg2_hot_path_hbm_traffic.txt: FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 of the call's
+# kernels (main + finishing kernel).
+TRAFFIC_KIB_PER_LAUNCH_CFG2 = {
     "absmax": (38243.1 + 5.0) * 2.0 + 50.1,
     "quant_error": (38284.6 + 27.7) * 2.0 + 68.6 + 0.1,
     "fake_quant": (38253.9 + 2.5) * 2.0 + 19110.0 + 1.2,
@@ -43,92 +48,10 @@ TRAFFIC_KIB_PER_LAUNCH = {
 }
 
 
-class Layer:
-    """Device buffers of one linear layer; allocated once, reused by every step."""
-
-    def __init__(self, torch, mpq, idx, name, a, w, bits_a, bits_w):
-        self.idx, self.name, self.bits_a, self.bits_w = idx, name, bits_a, bits_w
-        self.M, self.K = a.shape
-        self.N = w.shape[0]
-        self.a = torch.from_numpy(a).cuda()
-        self.w = torch.from_numpy(w).cuda()
-        dev = self.a.device
-        f32, i8, u8, f64 = torch.float32, torch.int8, torch.uint8, torch.float64
-        self.am_a = torch.empty(1, dtype=f32, device=dev)
-        self.am_w = torch.empty(self.N, dtype=f32, device=dev)
-        self.sse_a = torch.empty((1, 7), dtype=f64, device=dev)
-        self.sse_w = torch.empty((self.N, 7), dtype=f64, device=dev)
-        self.w_noisy = torch.empty_like(self.w)
-        self.a_codes = torch.empty((self.M, self.K), dtype=i8, device=dev)
-        self.w_store = 4 if bits_w <= 4 else 8
-        self.w_codes = (torch.empty((self.N, self.K // 2), dtype=u8, device=dev) if self.w_store == 4
-                        else torch.empty((self.N, self.K), dtype=i8, device=dev))
-        self.s_a = torch.empty(1, dtype=f32, device=dev)
-        self.s_w = torch.empty(self.N, dtype=f32, device=dev)
-        self.y = torch.empty((self.M, self.N), dtype=f32, device=dev)
-        # reference output of the unquantized layer, computed once outside the timed region
-        self.y_ref = self.a @ self.w.t()
-        self.score = torch.empty(1, dtype=f64, device=dev)
-
-    # algorithmic HBM bytes of each call of this layer (one read of every input, one write of
-    # every output, nothing else)
-    def bytes(self):
-        mk, nk, mn = self.M * self.K, self.N * self.K, self.M * self.N
-        wb = nk * self.w_store // 8
-        return {
-            "absmax": 4 * mk + 4 * nk,
-            "quant_error": 4 * mk + 4 * nk,
-            "noise_inject": 8 * nk,
-            "fake_quant": (4 * mk + mk) + (4 * nk + wb),
-            "qgemm": mk + wb + 4 * mn,
-            "sse_pair": 8 * mn,
-        }
-
-    # the part of bytes() that the main-stream launch of each call moves (activation side)
-    def main_bytes(self):
-        mk, nk, mn = self.M * self.K, self.N * self.K, self.M * self.N
-        wb = nk * self.w_store // 8
-        return {"absmax": 4 * mk, "quant_error": 4 * mk, "fake_quant": 5 * mk,
-                "qgemm": mk + wb + 4 * mn, "sse_pair": 8 * mn}
-
-    def ops(self):
-        return 2 * self.M * self.N * self.K
-
-
-def run_layer(mpq, L, ws_a, ws_w, rec, torch, side):
-    """The hot path on one layer.  rec(call_name) -> context manager that times the call.
-
-    The weight-side calls (small tensors, latency-bound launches) go to the side stream and overlap
-    the activation-side calls on the main stream; the GEMM waits for both.  Tensors of the two
-    sides are independent, each side has its own workspace."""
-    P = mpq
-    main = torch.cuda.current_stream()
-    side.wait_stream(main)  # the previous layer's GEMM has consumed what this side overwrites next
-    with torch.cuda.stream(side):
-        P.calibrate_absmax(L.w, P.PER_ROW, out=L.am_w)
-        P.quant_error(L.w, L.am_w, 2, 8, P.PER_ROW, out=L.sse_w, ws=ws_w)
-        P.noise_inject(L.w, L.am_w, L.bits_w, LAMBDA, 2302, L.idx, P.PER_ROW, out=L.w_noisy)
-        if L.w_store == 4:
-            P.fake_quant(L.w, L.am_w, L.bits_w, P.PER_ROW, want_y=False, packed4=L.w_codes)
-        else:
-            P.fake_quant(L.w, L.am_w, L.bits_w, P.PER_ROW, want_y=False, codes=L.w_codes)
-        P.scale_from_absmax(L.am_w, L.bits_w, out=L.s_w)
-    with rec("absmax"):
-        P.calibrate_absmax(L.a, P.PER_TENSOR, out=L.am_a, ws=ws_a)
-    with rec("quant_error"):
-        P.quant_error(L.a, L.am_a, 2, 8, P.PER_TENSOR, out=L.sse_a, ws=ws_a)
-    with rec("fake_quant"):
-        P.fake_quant(L.a, L.am_a, L.bits_a, P.PER_TENSOR, want_y=False, codes=L.a_codes)
-    P.scale_from_absmax(L.am_a, L.bits_a, out=L.s_a)
-    main.wait_stream(side)
-    with rec("qgemm"):
-        P.qgemm(L.a_codes, L.w_codes, L.s_a, L.s_w, L.w_store, P.PER_ROW, y=L.y, ws=ws_a)
-    with rec("sse_pair"):
-        P.sse_pair(L.y, L.y_ref, out=L.score, ws=ws_a)
-
-
+# ------------------------------------------------------------------------------------------------
+# timing helpers
 class NullRec:
-    def __call__(self, name):
+    def __call__(self, name, nbytes=0, ops=0):
         return self
 
     def __enter__(self):
@@ -139,14 +62,21 @@ class NullRec:
 
 
 class EventRec:
-    """Brackets selected calls with HIP events on the stream the kernels are launched on
-    (torch's current stream, which is the stream handed to every libmpq call)."""
+    """Brackets selected calls with HIP events on the stream the kernels are launched on (torch's
+    current stream, which is the stream handed to every libmpq call).  Also adds up the algorithmic
+    bytes / integer ops the bracketed launches were declared with."""
 
     def __init__(self, torch, only=None):
         self.torch, self.only, self.pairs, self.cur = torch, only, [], None
+        self.bytes, self.ops, self.count = {}, {}, {}
+        self._open = None
 
-    def __call__(self, name):
+    def __call__(self, name, nbytes=0, ops=0):
         self.cur = name
+        if self.only is None or name in self.only:
+            self.bytes[name] = self.bytes.get(name, 0) + nbytes
+            self.ops[name] = self.ops.get(name, 0) + ops
+            self.count[name] = self.count.get(name, 0) + 1
         return self
 
     def __enter__(self):
@@ -172,11 +102,322 @@ class EventRec:
         return out
 
 
+def measure(torch, step, snapshot, steps, warmup):
+    """Warm-up, HIP-graph capture of one step, `steps` timed replays, then the same steps launched
+    eagerly with HIP events around the dominant call.  Returns a dict of measurements."""
+    null = NullRec()
+    for _ in range(max(warmup - 1, 0)):
+        step(null)
+
+    def step_behind_a_blocker(rec):
+        # a ~1.5 ms spin kernel goes first, so that the host has enqueued (most of) the step before
+        # the GPU starts on it and the events bracket back-to-back kernels, not host launch gaps
+        torch.cuda._sleep(3_500_000)
+        step(rec)
+
+    probe = EventRec(torch)
+    step_behind_a_blocker(probe)
+    torch.cuda.synchronize()
+    per_call_ms = probe.totals_ms()
+    dominant = max(per_call_ms, key=per_call_ms.get)
+
+    # A step is hundreds of kernel launches of a few microseconds each: issued one by one from
+    # Python the host, not the GPU, sets the pace.  The step is therefore captured once into a HIP
+    # graph (the library records kernels only, no memset nodes) and the timed region replays it.
+    eager_ref = snapshot()
+    launch_mode, graph = "hip_graph", None
+
+    def same_as_eager():
+        for got, want in zip(snapshot(), eager_ref):
+            if not torch.equal(got, want):
+                raise RuntimeError("graph replay differs from the eager result")
+
+    try:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step(null)
+        graph.replay()
+        torch.cuda.synchronize()
+        same_as_eager()
+    except Exception as e:  # capture not possible here: time eager launches instead, and say so
+        print("bench.py: HIP graph path unavailable (%s); timing eager launches" % e, file=sys.stderr)
+        graph, launch_mode = None, "eager"
+        torch.cuda.synchronize()
+
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        if graph is not None:
+            graph.replay()
+        else:
+            step(null)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    if graph is not None:
+        same_as_eager()
+
+    # kernel-level timing for the roofline: the same steps launched eagerly right after, events
+    # around every launch of the dominant call and of qgemm (events cannot sit inside a replay)
+    rec = EventRec(torch, only={dominant, "qgemm"})
+    for _ in range(steps):
+        step_behind_a_blocker(rec)
+        torch.cuda.synchronize()
+    return {"ms_per_step": wall * 1e3 / steps, "launch": launch_mode, "probe": probe, "rec": rec,
+            "dominant": dominant, "steps": steps}
+
+
+def roofline_of(m, traffic_kib=None):
+    rec, dom, steps = m["rec"], m["dominant"], m["steps"]
+    ms = rec.totals_ms()[dom] / steps
+    n_launch = rec.count[dom] / steps
+    if dom == "qgemm":
+        roof = {"bound": "mfma", "achieved": rec.ops[dom] / steps / (ms * 1e-3) / 1e12, "peak": INT8_PEAK_TOPS,
+                "unit": "TOP/s", "algorithmic_per_launch": rec.ops[dom] / steps / n_launch}
+    else:
+        roof = {"bound": "hbm", "achieved": rec.bytes[dom] / steps / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "algorithmic_per_launch": rec.bytes[dom] / steps / n_launch}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    t = None if traffic_kib is None else traffic_kib.get(dom)
+    roof["traffic"] = None if t is None else t * 1024.0
+    roof["kernel"] = dom
+    roof["avg_launch_us"] = ms * 1e3 / n_launch
+    if dom == "quant_error":
+        # the sweep is co-bound by the vector ALUs: 29 lane-operations per element (7 bit-widths x
+        # 4 + one clip) against a peak of 39.3 T lane-op/s
+        rate = rec.bytes[dom] / steps / 4 * 29 / (ms * 1e-3) / 1e12
+        roof["alu"] = {"lane_ops_per_element": 29, "achieved_Tlaneop_s": rate,
+                       "peak_Tlaneop_s": ALU_PEAK_TLANEOPS, "frac": rate / ALU_PEAK_TLANEOPS}
+    return roof
+
+
+def gemm_summary(m):
+    rec, steps = m["rec"], m["steps"]
+    if "qgemm" not in rec.count:
+        return None
+    ms = rec.totals_ms()["qgemm"] / steps
+    tops = rec.ops["qgemm"] / steps / (ms * 1e-3) / 1e12
+    return {"tops": tops, "frac_of_int8_mfma_peak": tops / INT8_PEAK_TOPS, "ms_per_step": ms}
+
+
+# ------------------------------------------------------------------------------------------------
+# configurations 2 and 3: a stack of linear layers, whole path per layer
+class Layer:
+    """Device buffers of one linear layer; allocated once, reused by every step."""
+
+    def __init__(self, torch, idx, name, a, w, bits_a, bits_w, w_gran):
+        self.idx, self.name, self.bits_a, self.bits_w, self.w_gran = idx, name, bits_a, bits_w, w_gran
+        self.M, self.K = a.shape
+        self.N = w.shape[0]
+        self.a = torch.from_numpy(a).cuda()
+        self.w = torch.from_numpy(w).cuda()
+        dev = self.a.device
+        f32, i8, u8, f64 = torch.float32, torch.int8, torch.uint8, torch.float64
+        nch = self.N if w_gran == 1 else 1
+        self.am_a = torch.empty(1, dtype=f32, device=dev)
+        self.am_w = torch.empty(nch, dtype=f32, device=dev)
+        self.sse_a = torch.empty((1, 7), dtype=f64, device=dev)
+        self.sse_w = torch.empty((nch, 7), dtype=f64, device=dev)
+        self.w_noisy = torch.empty_like(self.w)
+        self.a_codes = torch.empty((self.M, self.K), dtype=i8, device=dev)
+        self.w_store = 4 if bits_w <= 4 else 8
+        self.w_codes = (torch.empty((self.N, self.K // 2), dtype=u8, device=dev) if self.w_store == 4
+                        else torch.empty((self.N, self.K), dtype=i8, device=dev))
+        self.s_a = torch.empty(1, dtype=f32, device=dev)
+        self.s_w = torch.empty(nch, dtype=f32, device=dev)
+        self.y = torch.empty((self.M, self.N), dtype=f32, device=dev)
+        # reference output of the unquantized layer, computed once outside the timed region
+        self.y_ref = self.a @ self.w.t()
+        self.score = torch.empty(1, dtype=f64, device=dev)
+
+    # algorithmic HBM bytes: one read of every input, one write of every output, nothing else
+    def bytes(self):
+        mk, nk, mn = self.M * self.K, self.N * self.K, self.M * self.N
+        wb = nk * self.w_store // 8
+        return {"absmax": 4 * mk + 4 * nk, "quant_error": 4 * mk + 4 * nk, "noise_inject": 8 * nk,
+                "fake_quant": (4 * mk + mk) + (4 * nk + wb), "qgemm": mk + wb + 4 * mn, "sse_pair": 8 * mn}
+
+    def ops(self):
+        return 2 * self.M * self.N * self.K
+
+
+def run_layer(P, L, ws_a, ws_w, rec, torch, side):
+    """The hot path on one layer.  The weight-side calls (small tensors, latency-bound launches) go
+    to the side stream and overlap the activation-side calls on the main stream; the GEMM waits
+    for both.  The two sides touch independent tensors and have their own workspaces."""
+    mk, mn = L.M * L.K, L.M * L.N
+    wb = L.N * L.K * L.w_store // 8
+    main = torch.cuda.current_stream()
+    side.wait_stream(main)  # the previous layer's GEMM has consumed what this side overwrites next
+    with torch.cuda.stream(side):
+        P.calibrate_absmax(L.w, L.w_gran, out=L.am_w, ws=ws_w)
+        P.quant_error(L.w, L.am_w, 2, 8, L.w_gran, out=L.sse_w, ws=ws_w)
+        P.noise_inject(L.w, L.am_w, L.bits_w, LAMBDA, 2302, L.idx, L.w_gran, out=L.w_noisy)
+        if L.w_store == 4:
+            P.fake_quant(L.w, L.am_w, L.bits_w, L.w_gran, want_y=False, packed4=L.w_codes)
+        else:
+            P.fake_quant(L.w, L.am_w, L.bits_w, L.w_gran, want_y=False, codes=L.w_codes)
+        P.scale_from_absmax(L.am_w, L.bits_w, out=L.s_w)
+    with rec("absmax", 4 * mk):
+        P.calibrate_absmax(L.a, P.PER_TENSOR, out=L.am_a, ws=ws_a)
+    with rec("quant_error", 4 * mk):
+        P.quant_error(L.a, L.am_a, 2, 8, P.PER_TENSOR, out=L.sse_a, ws=ws_a)
+    with rec("fake_quant", 5 * mk):
+        P.fake_quant(L.a, L.am_a, L.bits_a, P.PER_TENSOR, want_y=False, codes=L.a_codes)
+    P.scale_from_absmax(L.am_a, L.bits_a, out=L.s_a)
+    main.wait_stream(side)
+    with rec("qgemm", mk + wb + 4 * mn, L.ops()):
+        P.qgemm(L.a_codes, L.w_codes, L.s_a, L.s_w, L.w_store, L.w_gran, y=L.y, ws=ws_a)
+    with rec("sse_pair", 8 * mn):
+        P.sse_pair(L.y, L.y_ref, out=L.score, ws=ws_a)
+
+
+def workload_layers(torch, P, workloads, which):
+    layers = []
+    if which == "cfg2":
+        for idx, g in enumerate(workloads.CFG2):
+            a, w, ba, bw = workloads.cfg2_layer(idx)
+            layers.append(Layer(torch, idx, g.name, a, w, ba, bw, P.PER_ROW))
+        label = ("cfg2: ResNet-50-shaped conv-as-GEMM stack, batch 32, 8 layers, whole hot path per layer "
+                 "(absmax, quant_error b=2..8, noise, fake_quant, qgemm, sse_pair)")
+    else:
+        for idx, g in enumerate(workloads.CFG3):
+            a, w, ba, bw = workloads.cfg3_layer(idx)
+            layers.append(Layer(torch, idx, g.name, a, w, ba, bw, P.PER_TENSOR))
+        label = ("cfg3: BERT-base encoder linears, seq 384 x batch 32 (M = 12288), 4 layers, whole hot path "
+                 "per layer, per-tensor scales")
+    ws_a, ws_w = P.Workspace(), P.Workspace()
+    ws_a.get(1 << 22)
+    ws_w.get(1 << 22)
+    side = torch.cuda.Stream()  # default priority
+
+    def step(rec):
+        for L in layers:
+            run_layer(P, L, ws_a, ws_w, rec, torch, side)
+        torch.cuda.current_stream().wait_stream(side)
+
+    def snapshot():
+        out = []
+        for L in layers:
+            out += [L.score.clone(), L.sse_a.clone(), L.sse_w.clone(), L.am_w.clone()]
+        return out
+
+    nbytes = sum(sum(L.bytes().values()) for L in layers)
+    ops = sum(L.ops() for L in layers)
+    return step, snapshot, nbytes, ops, label, layers
+
+
+# ------------------------------------------------------------------------------------------------
+# configuration 4: sensitivity sweep over the BERT-large weight set
+def workload_cfg4(torch, P, workloads):
+    tensors = [torch.from_numpy(w).cuda() for _, w in workloads.cfg4_tensors()]
+    dev = tensors[0].device
+    f32, f64 = torch.float32, torch.float64
+    am_t = [torch.empty(1, dtype=f32, device=dev) for _ in tensors]
+    am_r = [torch.empty(t.shape[0], dtype=f32, device=dev) for t in tensors]
+    sse_t = [torch.empty((1, 7), dtype=f64, device=dev) for _ in tensors]
+    sse_r = [torch.empty((t.shape[0], 7), dtype=f64, device=dev) for t in tensors]
+    noisy = {tuple(t.shape): torch.empty_like(t) for t in tensors}  # one output buffer per shape
+    ws = P.Workspace()
+    ws.get(1 << 22)
+
+    def step(rec):
+        for i, t in enumerate(tensors):
+            n = t.numel()
+            with rec("absmax", 8 * n):
+                P.calibrate_absmax(t, P.PER_TENSOR, out=am_t[i], ws=ws)
+                P.calibrate_absmax(t, P.PER_ROW, out=am_r[i])
+            with rec("quant_error", 8 * n):
+                P.quant_error(t, am_t[i], 2, 8, P.PER_TENSOR, out=sse_t[i], ws=ws)
+                P.quant_error(t, am_r[i], 2, 8, P.PER_ROW, out=sse_r[i], ws=ws)
+            with rec("noise_inject", 7 * 8 * n):
+                for b in range(2, 9):
+                    P.noise_inject(t, am_r[i], b, LAMBDA, 2302, i, P.PER_ROW, out=noisy[tuple(t.shape)])
+
+    def snapshot():
+        return [s.clone() for s in sse_t] + [s.clone() for s in sse_r[:8]]
+
+    n_total = sum(t.numel() for t in tensors)
+    label = ("cfg4: sensitivity sweep over 96 BERT-large weight tensors (302 M elements): absmax + quant_error "
+             "b=2..8 per tensor and per output channel, noise at every b")
+    return step, snapshot, n_total * (8 + 8 + 56), 0, label
+
+
+# ------------------------------------------------------------------------------------------------
+# configuration 5: candidate scoring on a BERT-large FFN block
+def workload_cfg5(torch, P, workloads):
+    x, w1, w2 = workloads.cfg5_tensors()
+    cands = workloads.cfg5_candidates()
+    dx, dw1, dw2 = torch.from_numpy(x).cuda(), torch.from_numpy(w1).cuda(), torch.from_numpy(w2).cuda()
+    dev = dx.device
+    M, K1 = dx.shape
+    N1, N2 = dw1.shape[0], dw2.shape[0]
+    f32, i8, u8, f64 = torch.float32, torch.int8, torch.uint8, torch.float64
+    gelu = torch.nn.functional.gelu
+    y_ref = gelu(dx @ dw1.t()) @ dw2.t()
+    am_x, am_h = torch.empty(1, dtype=f32, device=dev), torch.empty(1, dtype=f32, device=dev)
+    am_w1, am_w2 = torch.empty(1, dtype=f32, device=dev), torch.empty(1, dtype=f32, device=dev)
+    s = [torch.empty(1, dtype=f32, device=dev) for _ in range(4)]
+    cx = torch.empty((M, K1), dtype=i8, device=dev)
+    ch = torch.empty((M, N1), dtype=i8, device=dev)
+    cw1, pw1 = torch.empty((N1, K1), dtype=i8, device=dev), torch.empty((N1, K1 // 2), dtype=u8, device=dev)
+    cw2, pw2 = torch.empty((N2, N1), dtype=i8, device=dev), torch.empty((N2, N1 // 2), dtype=u8, device=dev)
+    h = torch.empty((M, N1), dtype=f32, device=dev)
+    g = torch.empty((M, N1), dtype=f32, device=dev)
+    y = torch.empty((M, N2), dtype=f32, device=dev)
+    scores = torch.empty(len(cands), dtype=f64, device=dev)
+    ws = P.Workspace()
+    ws.get(1 << 22)
+
+    def quant_w(rec, dw, am, b, codes, packed, sc):
+        with rec("fake_quant", int(dw.numel() * (4.5 if b <= 4 else 5))):
+            if b <= 4:
+                P.fake_quant(dw, am, b, want_y=False, packed4=packed)
+            else:
+                P.fake_quant(dw, am, b, want_y=False, codes=codes)
+        P.scale_from_absmax(am, b, out=sc)
+        return (packed, 4) if b <= 4 else (codes, 8)
+
+    def step(rec):
+        with rec("absmax", 4 * (dx.numel() + dw1.numel() + dw2.numel())):
+            P.calibrate_absmax(dx, out=am_x, ws=ws)
+            P.calibrate_absmax(dw1, out=am_w1, ws=ws)
+            P.calibrate_absmax(dw2, out=am_w2, ws=ws)
+        for c, (bw1, ba1, bw2, ba2) in enumerate(cands):
+            q1, st1 = quant_w(rec, dw1, am_w1, bw1, cw1, pw1, s[0])
+            q2, st2 = quant_w(rec, dw2, am_w2, bw2, cw2, pw2, s[1])
+            with rec("fake_quant", 5 * dx.numel()):
+                P.fake_quant(dx, am_x, ba1, want_y=False, codes=cx)
+            P.scale_from_absmax(am_x, ba1, out=s[2])
+            with rec("qgemm", M * K1 + N1 * K1 * st1 // 8 + 4 * M * N1, 2 * M * N1 * K1):
+                P.qgemm(cx, q1, s[2], s[0], st1, y=h, ws=ws)
+            g.copy_(gelu(h))  # the activation is not a libmpq call: torch, on the same stream
+            with rec("absmax", 4 * g.numel()):
+                P.calibrate_absmax(g, out=am_h, ws=ws)
+            with rec("fake_quant", 5 * g.numel()):
+                P.fake_quant(g, am_h, ba2, want_y=False, codes=ch)
+            P.scale_from_absmax(am_h, ba2, out=s[3])
+            with rec("qgemm", M * N1 + N2 * N1 * st2 // 8 + 4 * M * N2, 2 * M * N2 * N1):
+                P.qgemm(ch, q2, s[3], s[1], st2, y=y, ws=ws)
+            with rec("sse_pair", 8 * y.numel()):
+                P.sse_pair(y, y_ref, out=scores[c:c + 1], ws=ws)
+
+    def snapshot():
+        return [scores.clone()]
+
+    per_cand = (4.75 * (dw1.numel() + dw2.numel()) + 5 * dx.numel() + (M * K1 + N1 * K1 + 4 * M * N1)
+                + 4 * M * N1 + 5 * M * N1 + (M * N1 + N2 * N1 + 4 * M * N2) + 8 * M * N2)
+    nbytes = int(len(cands) * per_cand + 4 * (dx.numel() + dw1.numel() + dw2.numel()))
+    ops = len(cands) * (2 * M * N1 * K1 + 2 * M * N2 * N1)
+    label = ("cfg5: 64 candidate bit configurations of a BERT-large FFN block (1024 -> 4096 -> 1024) at "
+             "M = 16384, back to back: re-quantize, qgemm, GELU (torch), re-quantize, qgemm, output SSE")
+    return step, snapshot, nbytes, ops, label, len(cands)
+
+
+# ------------------------------------------------------------------------------------------------
 def cpu_baseline(workloads, sample_rows):
-    """The oracle, as it stands, over the same path on a bounded sample: the first `sample_rows`
-    activation rows of every layer with the full weight tensors.  Layers run on a thread pool
-    (the oracle itself is single threaded; ctypes releases the GIL)."""
-    import numpy as np
+    """The oracle, as it stands, over the configuration-2 path on a bounded sample: the first
+    `sample_rows` activation rows of every layer with the full weight tensors.  Layers run on a
+    thread pool (the oracle itself is single threaded; ctypes releases the GIL)."""
     import oracle
 
     def one(idx):
@@ -210,8 +451,8 @@ def cpu_baseline(workloads, sample_rows):
     total = sum(r[0] for r in res)
     return {
         "value": total / wall / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
-        "sample": "first %d activation rows of each of the 8 layers, full weights; %.1f s wall, "
-                  "%.1f s summed over threads" % (sample_rows, wall, sum(r[1] for r in res)),
+        "sample": "cfg2 path on the first %d activation rows of each of the 8 layers, full weights; "
+                  "%.1f s wall, %.1f s summed over threads" % (sample_rows, wall, sum(r[1] for r in res)),
     }
 
 
@@ -220,10 +461,11 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", choices=["cfg2", "cfg3", "cfg4", "cfg5"], default="cfg2")
     ap.add_argument("--cpu-sample-rows", type=int, default=1024)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run a plain device copy of known size (231 MB) three times before the "
+                    help="also run a plain device copy of known size (225792 KiB) three times before the "
                          "warm-up: the reference that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -240,144 +482,49 @@ def main():
     torch.cuda.set_device(0)
     mpq.lib()
 
-    layers = []
-    for idx, g in enumerate(workloads.CFG2):
-        a, w, ba, bw = workloads.cfg2_layer(idx)
-        layers.append(Layer(torch, mpq, idx, g.name, a, w, ba, bw))
-        del a, w
-    ws_a, ws_w = mpq.Workspace(), mpq.Workspace()
-    ws_a.get(1 << 22)
-    ws_w.get(1 << 22)
-    side = torch.cuda.Stream()  # default priority
+    extra = {}
+    traffic = None
+    layers = None
+    if args.workload in ("cfg2", "cfg3"):
+        step, snapshot, nbytes, ops, label, layers = workload_layers(torch, mpq, workloads, args.workload)
+        traffic = TRAFFIC_KIB_PER_LAUNCH_CFG2 if args.workload == "cfg2" else None
+    elif args.workload == "cfg4":
+        step, snapshot, nbytes, ops, label = workload_cfg4(torch, mpq, workloads)
+    else:
+        step, snapshot, nbytes, ops, label, ncand = workload_cfg5(torch, mpq, workloads)
+        extra["candidates_per_step"] = ncand
+        args.steps = min(args.steps, 5)   # one step is 64 candidates (~20 ms); keep the GPU time bounded
     torch.cuda.synchronize()
 
-    if args.calibrate_copy:
+    if args.calibrate_copy and layers is not None:
         dst = torch.empty_like(layers[0].a)
         for _ in range(3):
-            dst.copy_(layers[0].a)   # plain copy kernel: reads and writes layers[0].a.numel() * 4 bytes
+            dst.copy_(layers[0].a)   # plain copy: reads and writes layers[0].a.numel() * 4 bytes
         torch.cuda.synchronize()
         del dst
 
-    def step(rec):
-        for L in layers:
-            run_layer(mpq, L, ws_a, ws_w, rec, torch, side)
-        torch.cuda.current_stream().wait_stream(side)
-
-    # warm-up; the last warm-up step is timed per call to find the dominant one
-    null = NullRec()
-    for _ in range(max(args.warmup - 1, 0)):
-        step(null)
-    def step_behind_a_blocker(rec):
-        """Eager step for kernel-level timing: a ~1.5 ms spin kernel goes first, so that the host has
-        enqueued the whole step before the GPU starts on it and the HIP events bracket back-to-back
-        kernels instead of host launch gaps."""
-        torch.cuda._sleep(3_500_000)
-        step(rec)
-
-    probe = EventRec(torch)
-    step_behind_a_blocker(probe)
-    torch.cuda.synchronize()
-    per_call_ms = probe.totals_ms()
-    dominant = max(per_call_ms, key=per_call_ms.get)
-
-    # One step = ~130 kernel launches of a few microseconds each: issued one by one from Python the
-    # host, not the GPU, sets the pace.  The step is therefore captured once into a HIP graph (both
-    # streams; the library records kernels only, no memset nodes) and the timed region replays it.
-    def snapshot():
-        return [(L.score.clone(), L.sse_a.clone(), L.sse_w.clone(), L.am_w.clone()) for L in layers]
-
-    eager_ref = snapshot()
-    launch_mode = "hip_graph"
-    graph = None
-    try:
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            step(null)
-        graph.replay()
-        torch.cuda.synchronize()
-        for got, want in zip(snapshot(), eager_ref):
-            for g_, w_ in zip(got, want):
-                if not torch.equal(g_, w_):
-                    raise RuntimeError("graph replay differs from the eager result")
-    except Exception as e:  # capture not possible here: time eager launches instead, and say so
-        print("bench.py: HIP graph path unavailable (%s); timing eager launches" % e, file=sys.stderr)
-        graph = None
-        launch_mode = "eager"
-        torch.cuda.synchronize()
-
-    # timed region: exactly `steps` steps
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        if graph is not None:
-            graph.replay()
-        else:
-            step(null)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms_per_step = wall * 1e3 / args.steps
-    if graph is not None:
-        for got, want in zip(snapshot(), eager_ref):
-            for g_, w_ in zip(got, want):
-                if not torch.equal(g_, w_):
-                    raise RuntimeError("graph replay differs from the eager result after the timed region")
-
-    # kernel-level timing for the roofline: the same `steps` steps launched eagerly right after,
-    # HIP events around every launch of the dominant call and of qgemm on the stream they run on
-    # (events cannot be recorded inside a graph replay)
-    rec = EventRec(torch, only={dominant, "qgemm"})
-    for _ in range(args.steps):
-        step_behind_a_blocker(rec)
-        torch.cuda.synchronize()
-
-    call_bytes = {c: sum(L.bytes()[c] for L in layers) for c in CALLS}
-    main_bytes = {c: sum(L.main_bytes()[c] for L in layers) for c in layers[0].main_bytes()}
-    step_bytes = sum(call_bytes.values())
-    timed = rec.totals_ms()
-    dom_ms_per_step = timed[dominant] / args.steps
-    gemm_ms_per_step = timed["qgemm"] / args.steps
-    gemm_ops = sum(L.ops() for L in layers)
-    n_launch = len(layers)  # one main-stream launch of the dominant call per layer
-    if dominant == "qgemm":
-        roof = {"bound": "mfma", "achieved": gemm_ops / (gemm_ms_per_step * 1e-3) / 1e12,
-                "peak": INT8_PEAK_TOPS, "unit": "TOP/s"}
-    else:
-        roof = {"bound": "hbm", "achieved": main_bytes[dominant] / (dom_ms_per_step * 1e-3) / 1e9,
-                "peak": HBM_PEAK_GBS, "unit": "GB/s"}
-    roof["frac"] = roof["achieved"] / roof["peak"]
-    t_kib = TRAFFIC_KIB_PER_LAUNCH.get(dominant)
-    roof["traffic"] = None if t_kib is None else t_kib * 1024.0
-    roof["kernel"] = dominant
-    roof["avg_launch_us"] = dom_ms_per_step * 1e3 / n_launch
-    roof["algorithmic_per_launch"] = (gemm_ops if dominant == "qgemm" else main_bytes[dominant]) / n_launch
-    if dominant == "quant_error":
-        # the sweep is co-bound by the vector ALUs: 29 lane-operations per element (7 bit-widths x
-        # 4 + one clip); peak 256 CUs x 64 lanes x 2.4 GHz = 39.3 T lane-op/s without packed math
-        elems = main_bytes[dominant] / 4
-        roof["alu"] = {"lane_ops_per_element": 29, "achieved_Tlaneop_s": elems * 29 / (dom_ms_per_step * 1e-3) / 1e12,
-                       "peak_Tlaneop_s": 39.3216,
-                       "frac": elems * 29 / (dom_ms_per_step * 1e-3) / 1e12 / 39.3216}
-
+    m = measure(torch, step, snapshot, args.steps, args.warmup)
+    ms = m["ms_per_step"]
+    probe_ms = m["probe"].totals_ms()
     out = {
         "metric": METRIC,
-        "value": step_bytes / (ms_per_step * 1e-3) / 1e9,
+        "value": nbytes / (ms * 1e-3) / 1e9,
         "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step,
+        "ms_per_step": ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32 elementwise, int8 x int8 -> int32 GEMM",
         "data": "synthetic",
-        "config": {"workload": "cfg2: ResNet-50-shaped conv-as-GEMM stack, batch 32, 8 layers, "
-                               "whole hot path per layer (absmax, quant_error b=2..8, noise, fake_quant, qgemm, sse_pair)",
-                   "step_algorithmic_bytes": step_bytes, "step_gemm_ops": gemm_ops},
-        "launch": launch_mode,
-        "qgemm": {"tops": gemm_ops / (gemm_ms_per_step * 1e-3) / 1e12,
-                  "frac_of_int8_mfma_peak": gemm_ops / (gemm_ms_per_step * 1e-3) / 1e12 / INT8_PEAK_TOPS,
-                  "ms_per_step": gemm_ms_per_step},
-        "main_stream_call_ms_probe_step": {k: round(v, 4) for k, v in per_call_ms.items()},
-        "main_stream_call_gbs_probe_step": {k: round(main_bytes[k] / (v * 1e-3) / 1e9, 1) for k, v in per_call_ms.items()},
-        "roofline": roof,
+        "config": {"workload": label, "step_algorithmic_bytes": nbytes, "step_gemm_ops": ops},
+        "launch": m["launch"],
+        "qgemm": gemm_summary(m),
+        "timed_call_ms_probe_step": {k: round(v, 4) for k, v in probe_ms.items()},
+        "timed_call_gbs_probe_step": {k: round(m["probe"].bytes[k] / (v * 1e-3) / 1e9, 1)
+                                      for k, v in probe_ms.items()},
+        "roofline": roofline_of(m, traffic),
     }
+    if "candidates_per_step" in extra:
+        out["candidates_per_s"] = extra["candidates_per_step"] / (ms * 1e-3)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(workloads, args.cpu_sample_rows)
     print(json.dumps(out))

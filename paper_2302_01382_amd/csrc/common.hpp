@@ -88,6 +88,15 @@ __device__ __forceinline__ float wave_sum(float v) {
   return (r0 + r1) + (r2 + r3);
 }
 
+// Sum over each aligned group of 16 lanes (one DPP row); every lane of the group gets the result.
+__device__ __forceinline__ float row16_sum(float v) {
+  v += dpp<kQuadSwap1>(v);
+  v += dpp<kQuadSwap2>(v);
+  v += dpp<kRowHalfMirror>(v);
+  v += dpp<kRowMirror>(v);
+  return v;
+}
+
 __device__ __forceinline__ float wave_max(float v) {
   v = fmaxf(v, dpp<kQuadSwap1>(v));
   v = fmaxf(v, dpp<kQuadSwap2>(v));

@@ -212,7 +212,6 @@ __global__ __launch_bounds__(kGemmThreads) void qgemm_k(const int8_t* __restrict
 
 __device__ __attribute__((aligned(16))) int g_zero16[4];  // never written: zero fill for k tails
 
-constexpr int DBK = 128;  // k bytes per stage
 
 // The direct-to-LDS load and its wait are written as inline assembly on purpose: when the
 // compiler sees the load it cannot tell which LDS bytes are in flight once more than a handful of
@@ -222,15 +221,25 @@ constexpr int DBK = 128;  // k bytes per stage
 // youngest n wave-loads of this wave have landed.
 // lds_byte_off must be wave-uniform (it travels in M0); lane l's 16 bytes land at +16 l.
 __device__ __forceinline__ void dma16(const char* src, unsigned lds_byte_off) {
-  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_byte_off) : "memory");
+  // s_nop: the one wait state the ISA asks for between a write of M0 and an LDS-DMA that reads it
+  // (the compiler's hazard pass does not look inside inline assembly)
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_byte_off) : "memory");
 }
 template <int N_>
 __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N_) : "memory");
 }
 
-template <int BM, int BN, int WM, int WN, int NSTAGE, bool W4>
+// KB: k bytes per stage (128 or 64)
+template <int BM, int BN, int WM, int WN, int NSTAGE, bool W4, int KB>
 struct DmaCfg {
+  static constexpr int DBK = KB;
+  static constexpr int CPR = KB / 16;                 // 16-byte chunks per int8 tile row (8 | 4)
+  static constexpr int RPI = 64 / CPR;                // tile rows one wave-load covers (8 | 16)
+  static constexpr int SH = CPR == 8 ? 1 : 2;         // swizzle: slot = chunk ^ ((row >> SH) & (CPR-1))
+  static constexpr int PCPR = KB / 32;                // 16-byte chunks per packed-int4 tile row (4 | 2)
+  static constexpr int PRPI = 64 / PCPR;              // packed rows per wave-load (16 | 32)
+  static constexpr int PSH = PCPR == 4 ? 2 : 3;
   static constexpr int NW = WM * WN;
   static constexpr int NT = NW * 64;
   static constexpr int TM = BM / WM, TN = BN / WN;   // per-wave tile
@@ -240,84 +249,98 @@ struct DmaCfg {
   static constexpr int B_STAGE = BN * B_ROW;
   static constexpr int STAGE = A_STAGE + B_STAGE;
   static constexpr int LDS_BYTES = NSTAGE * STAGE;
-  static constexpr int NLA = BM / 8;                  // wave-loads per A stage (8 rows each)
-  static constexpr int NLB = W4 ? BN / 16 : BN / 8;   // wave-loads per W stage
+  static constexpr int NLA = BM / RPI;                // wave-loads per A stage
+  static constexpr int NLB = W4 ? BN / PRPI : BN / RPI;  // wave-loads per W stage
   static constexpr int LPW = (NLA + NLB) / NW;        // wave-loads per wave per stage
   static_assert(NLA % NW == 0 && NLB % NW == 0, "loads must divide evenly over the waves");
   static_assert(TM % 32 == 0 && TN % 32 == 0, "wave tile is a multiple of 32 x 32");
+  static_assert(KB == 128 || KB == 64, "k tile of 128 or 64 bytes");
   static_assert((NSTAGE - 1) * LPW < 64, "vmcnt is a 6-bit counter");
 };
 
-// lds_stage_off: LDS byte offset of the stage (wave-uniform); wave_u: wave id in an SGPR
+// What one wave fetches per stage, fixed for the whole k loop: for each of its wave-loads the
+// lane's source row (as a pointer to k = 0 of the chunk it owns) and the chunk's k offset.  Per
+// stage the lane then only adds k0 and checks the k tail.
 template <class C, bool W4>
-__device__ __forceinline__ void dma_issue_stage(unsigned lds_stage_off, const int8_t* __restrict__ A,
-                                                const uint8_t* __restrict__ W, int64_t M, int64_t N,
-                                                int64_t K, int64_t m0, int64_t n0, int64_t k0,
-                                                int wave_u, int lane) {
-  const char* zero = reinterpret_cast<const char*>(g_zero16);
-  {  // A tile: wave-load j covers rows 8j .. 8j+7
-    const int lr = lane >> 3;          // row within the 8-row group
+struct DmaPlan {
+  static constexpr int NA = C::NLA / C::NW, NB_ = C::NLB / C::NW;
+  const char* pa[NA];
+  const char* pb[NB_];
+  int ka[NA], kb[NB_];   // k of the lane's chunk within the tile (bytes of A / values of W)
+  unsigned wave_off;     // LDS offset of this wave's first wave-load within a stage region
+
+  __device__ __forceinline__ void init(const int8_t* __restrict__ A, const uint8_t* __restrict__ W,
+                                       int64_t M, int64_t N, int64_t K, int64_t m0, int64_t n0,
+                                       int wave_u, int lane) {
+    wave_off = (unsigned)wave_u * 1024u;
 #pragma unroll
-    for (int t = 0; t < C::NLA / C::NW; ++t) {
+    for (int t = 0; t < NA; ++t) {  // A tile: wave-load j covers RPI rows
       const int j = wave_u + t * C::NW;
-      const int c = (lane & 7) ^ (((8 * j + lr) >> 1) & 7);  // logical chunk this lane fetches
-      const int64_t kk = k0 + c * 16;
-      const bool live = kk < K;
-      int64_t r = m0 + 8 * j + lr;
-      if (r >= M) r = M - 1;
-      const char* src = live ? reinterpret_cast<const char*>(A) + r * K + kk : zero;
-      dma16(src, lds_stage_off + (unsigned)j * 1024u);
+      const int row = C::RPI * j + lane / C::CPR;
+      const int c = (lane % C::CPR) ^ ((row >> C::SH) & (C::CPR - 1));  // logical chunk this lane fetches
+      int64_t r = m0 + row;
+      if (r >= M) r = M - 1;  // rows past the edge re-read the last row; never stored
+      ka[t] = c * 16;
+      pa[t] = reinterpret_cast<const char*>(A) + r * K + ka[t];
+    }
+#pragma unroll
+    for (int t = 0; t < NB_; ++t) {
+      const int j = wave_u + t * C::NW;
+      if (!W4) {
+        const int row = C::RPI * j + lane / C::CPR;
+        const int c = (lane % C::CPR) ^ ((row >> C::SH) & (C::CPR - 1));
+        int64_t r = n0 + row;
+        if (r >= N) r = N - 1;
+        kb[t] = c * 16;
+        pb[t] = reinterpret_cast<const char*>(W) + r * K + kb[t];
+      } else {  // packed tile: wave-load j covers PRPI rows of KB/2 packed bytes
+        const int row = C::PRPI * j + lane / C::PCPR;
+        const int c = (lane % C::PCPR) ^ ((row >> C::PSH) & (C::PCPR - 1));  // logical chunk = 32 values
+        int64_t r = n0 + row;
+        if (r >= N) r = N - 1;
+        kb[t] = c * 32;
+        pb[t] = reinterpret_cast<const char*>(W) + r * (K >> 1) + (kb[t] >> 1);
+      }
     }
   }
-  if (!W4) {
-    const int lr = lane >> 3;
+
+  // requests the k tile starting at k0 into the stage at LDS offset lds_stage_off
+  __device__ __forceinline__ void issue(unsigned lds_stage_off, int64_t k0, int64_t K) const {
+    const char* zero = reinterpret_cast<const char*>(g_zero16);
 #pragma unroll
-    for (int t = 0; t < C::NLB / C::NW; ++t) {
-      const int j = wave_u + t * C::NW;
-      const int c = (lane & 7) ^ (((8 * j + lr) >> 1) & 7);
-      const int64_t kk = k0 + c * 16;
-      const bool live = kk < K;
-      int64_t r = n0 + 8 * j + lr;
-      if (r >= N) r = N - 1;
-      const char* src = live ? reinterpret_cast<const char*>(W) + r * K + kk : zero;
-      dma16(src, lds_stage_off + (unsigned)C::A_STAGE + (unsigned)j * 1024u);
+    for (int t = 0; t < NA; ++t) {
+      const char* src = (k0 + ka[t] < K) ? pa[t] + k0 : zero;
+      dma16(src, lds_stage_off + wave_off + (unsigned)(t * C::NW) * 1024u);
     }
-  } else {  // packed tile: wave-load j covers rows 16j .. 16j+15 of 64 packed bytes
-    const int lr = lane >> 2;
-    const int c = (lane & 3) ^ ((lr >> 2) & 3);   // logical 16-byte chunk = 32 values (16 j + lr: same bits)
-    const int64_t kk = k0 + c * 32;               // first k of the chunk
-    const bool live = kk < K;
 #pragma unroll
-    for (int t = 0; t < C::NLB / C::NW; ++t) {
-      const int j = wave_u + t * C::NW;
-      int64_t r = n0 + 16 * j + lr;
-      if (r >= N) r = N - 1;
-      const char* src = live ? reinterpret_cast<const char*>(W) + r * (K >> 1) + (kk >> 1) : zero;
-      dma16(src, lds_stage_off + (unsigned)C::A_STAGE + (unsigned)j * 1024u);
+    for (int t = 0; t < NB_; ++t) {
+      const char* src = (k0 + kb[t] < K) ? pb[t] + (W4 ? (k0 >> 1) : k0) : zero;
+      dma16(src, lds_stage_off + (unsigned)C::A_STAGE + wave_off + (unsigned)(t * C::NW) * 1024u);
     }
   }
-}
+};
 
 // operand fragments of k-substep s (32 k-values) of one stage
 template <class C, bool W4>
 __device__ __forceinline__ void dma_load_frags(const char* lds_stage, int s, int wm, int wn, int lane,
                                                v4i (&fa)[C::FM], v4i (&fb)[C::FN]) {
   const int l31 = lane & 31, g = lane >> 5;
-  const int ch = 2 * s + g;  // logical 16-byte chunk of the 128-byte row
+  constexpr int DBK = C::DBK;
+  const int ch = 2 * s + g;  // logical 16-byte chunk of the tile row
 #pragma unroll
   for (int i = 0; i < C::FM; ++i) {
     const int row = wm * C::TM + i * 32 + l31;
-    fa[i] = *reinterpret_cast<const v4i*>(lds_stage + row * DBK + ((ch ^ ((row >> 1) & 7)) << 4));
+    fa[i] = *reinterpret_cast<const v4i*>(lds_stage + row * DBK + ((ch ^ ((row >> C::SH) & (C::CPR - 1))) << 4));
   }
 #pragma unroll
   for (int j = 0; j < C::FN; ++j) {
     const int row = wn * C::TN + j * 32 + l31;
     if (!W4) {
-      fb[j] = *reinterpret_cast<const v4i*>(lds_stage + C::A_STAGE + row * DBK + ((ch ^ ((row >> 1) & 7)) << 4));
+      fb[j] = *reinterpret_cast<const v4i*>(lds_stage + C::A_STAGE + row * DBK + ((ch ^ ((row >> C::SH) & (C::CPR - 1))) << 4));
     } else {
       // 16 values = 8 packed bytes: half g of logical packed chunk s
       const uint2 pk = *reinterpret_cast<const uint2*>(lds_stage + C::A_STAGE + row * (DBK / 2) +
-                                                       ((s ^ ((row >> 2) & 3)) << 4) + g * 8);
+                                                       ((s ^ ((row >> C::PSH) & (C::PCPR - 1))) << 4) + g * 8);
       unsigned b0, b1, b2, b3;
       expand8(pk.x, b0, b1);
       expand8(pk.y, b2, b3);
@@ -326,31 +349,24 @@ __device__ __forceinline__ void dma_load_frags(const char* lds_stage, int s, int
   }
 }
 
-// all MFMAs of one stage; the fragments of substep s+1 are requested before the MFMAs of substep s
-// are issued, so the LDS latency hides behind the matrix pipe
-template <class C, bool W4>
-__device__ __forceinline__ void dma_compute_stage(const char* lds_stage, v16i (&acc)[C::FM][C::FN],
-                                                  int wm, int wn, int lane) {
-  constexpr int NSUB = DBK / 32;
-  v4i fa[2][C::FM], fb[2][C::FN];
-  dma_load_frags<C, W4>(lds_stage, 0, wm, wn, lane, fa[0], fb[0]);
+template <class C>
+__device__ __forceinline__ void dma_mfma_substep(v16i (&acc)[C::FM][C::FN], const v4i (&fa)[C::FM],
+                                                 const v4i (&fb)[C::FN]) {
 #pragma unroll
-  for (int s = 0; s < NSUB; ++s) {
-    if (s + 1 < NSUB) dma_load_frags<C, W4>(lds_stage, s + 1, wm, wn, lane, fa[(s + 1) & 1], fb[(s + 1) & 1]);
+  for (int i = 0; i < C::FM; ++i)
 #pragma unroll
-    for (int i = 0; i < C::FM; ++i)
-#pragma unroll
-      for (int j = 0; j < C::FN; ++j)
-        // W fragment as the row operand: the lane then holds 4 consecutive n per register
-        // group, which the epilogue stores as one 16-byte piece of a Y row
-        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[s & 1][j], fa[s & 1][i], acc[i][j], 0, 0, 0);
-  }
+    for (int j = 0; j < C::FN; ++j)
+      // W fragment as the row operand: the lane then holds 4 consecutive n per register group,
+      // which the epilogue stores as one 16-byte piece of a Y row
+      acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[j], fa[i], acc[i][j], 0, 0, 0);
 }
 
 // grid: 1-D over output tiles, N fastest; `swizzle_xcd` regroups block ids so that the blocks an
 // XCD receives (ids congruent mod 8) cover one contiguous range of tiles and share its L2.
-template <int BM, int BN, int WM, int WN, int NSTAGE, bool W4, bool VEC>
-__global__ __launch_bounds__(WM * WN * 64) void qgemm_dma(const int8_t* __restrict__ A,
+// MINW: waves the register allocation must leave room for on one SIMD (2 = two co-resident
+// 4-wave workgroups per CU)
+template <int BM, int BN, int WM, int WN, int NSTAGE, bool W4, bool VEC, int KB, int MINW>
+__global__ __launch_bounds__(WM * WN * 64, MINW) void qgemm_dma(const int8_t* __restrict__ A,
                                                           const void* __restrict__ Wv, int64_t M,
                                                           int64_t N, int64_t K,
                                                           const float* __restrict__ a_scale,
@@ -358,7 +374,8 @@ __global__ __launch_bounds__(WM * WN * 64) void qgemm_dma(const int8_t* __restri
                                                           int w_per_row, float* __restrict__ Y,
                                                           int32_t* __restrict__ ACC, int tiles_n,
                                                           int swizzle_xcd) {
-  using C = DmaCfg<BM, BN, WM, WN, NSTAGE, W4>;
+  using C = DmaCfg<BM, BN, WM, WN, NSTAGE, W4, KB>;
+  constexpr int DBK = KB;
   extern __shared__ __attribute__((aligned(16))) char lds[];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -378,20 +395,43 @@ __global__ __launch_bounds__(WM * WN * 64) void qgemm_dma(const int8_t* __restri
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
   const int KT = (int)((K + DBK - 1) / DBK);
-  // prologue: tiles 0 .. NSTAGE-2 (tiles past the end fetch zeros: harmless and keeps vmcnt uniform)
+  constexpr int NSUB = DBK / 32;
+  static_assert(NSUB % 2 == 0, "fragment double buffer assumes an even number of k substeps");
+  DmaPlan<C, W4> plan;
+  plan.init(A, Wb, M, N, K, m0, n0, wave, lane);
+
+  // Software pipeline.  Every stage holds a tile; tile t + NSTAGE is requested into the stage of
+  // tile t at the moment that stage has been read for the last time, which is BEFORE the MFMAs of
+  // the tile's last k substep are issued (their operands sit in registers by then).  The same
+  // point waits for tile t + 1, passes the barrier and requests the first fragments of tile t + 1,
+  // so that barrier skew, the address arithmetic of the loads and the LDS latency all hide behind
+  // the matrix pipe working off the queued MFMAs.
+  // (tiles past the end fetch zeros: harmless and keeps the vmcnt bookkeeping uniform)
 #pragma unroll
-  for (int p = 0; p < NSTAGE - 1; ++p)
-    dma_issue_stage<C, W4>(lds0 + p * C::STAGE, A, Wb, M, N, K, m0, n0, (int64_t)p * DBK, wave, lane);
+  for (int p = 0; p < NSTAGE; ++p) plan.issue(lds0 + p * C::STAGE, (int64_t)p * DBK, K);
+  wait_vmcnt<(NSTAGE - 1) * C::LPW>();  // this wave's share of tile 0 has landed
+  __syncthreads();                      // ... and everyone else's
+  v4i fa[2][C::FM], fb[2][C::FN];
+  dma_load_frags<C, W4>(lds, 0, wm, wn, lane, fa[0], fb[0]);
 
   for (int kt = 0; kt < KT; kt += NSTAGE) {
 #pragma unroll
     for (int u = 0; u < NSTAGE; ++u) {
       if (kt + u < KT) {  // block-uniform
-        wait_vmcnt<(NSTAGE - 2) * C::LPW>();  // this wave's share of tile kt+u has landed
-        __syncthreads();                    // everyone's share has landed; stage (u-1) is free again
-        dma_issue_stage<C, W4>(lds0 + ((u + NSTAGE - 1) % NSTAGE) * C::STAGE, A, Wb, M, N, K, m0, n0,
-                               (int64_t)(kt + u + NSTAGE - 1) * DBK, wave, lane);
-        dma_compute_stage<C, W4>(lds + u * C::STAGE, acc, wm, wn, lane);
+        const char* stage = lds + u * C::STAGE;
+#pragma unroll
+        for (int sub = 0; sub < NSUB; ++sub) {
+          if (sub + 1 < NSUB) {
+            dma_load_frags<C, W4>(stage, sub + 1, wm, wn, lane, fa[(sub + 1) & 1], fb[(sub + 1) & 1]);
+          } else {
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wave has read the stage for the last time
+            wait_vmcnt<(NSTAGE - 2) * C::LPW>();                // its share of the next tile has landed
+            __syncthreads();
+            plan.issue(lds0 + u * C::STAGE, (int64_t)(kt + u + NSTAGE) * DBK, K);
+            dma_load_frags<C, W4>(lds + ((u + 1) % NSTAGE) * C::STAGE, 0, wm, wn, lane, fa[0], fb[0]);
+          }
+          dma_mfma_substep<C>(acc, fa[sub & 1], fb[sub & 1]);
+        }
       }
     }
   }
@@ -401,6 +441,19 @@ __global__ __launch_bounds__(WM * WN * 64) void qgemm_dma(const int8_t* __restri
   // 4g .. 4g+3, the four consecutive n = 8g + 4 (l / 32) + 0..3.
   const float sa = Y ? a_scale[0] : 0.0f;
   const float sw0 = (Y && !w_per_row) ? w_scale[0] : 0.0f;
+  // all scales first: a load issued between stores would make the compiler wait for every store
+  // in flight before using it
+  float4 swv[C::FN][4];
+  if (VEC) {
+#pragma unroll
+    for (int j = 0; j < C::FN; ++j)
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const int64_t n = n0 + wn * C::TN + j * 32 + g4 * 8 + (lane >> 5) * 4;
+        swv[j][g4] = make_float4(sw0, sw0, sw0, sw0);
+        if (Y && w_per_row && n < N) swv[j][g4] = *reinterpret_cast<const float4*>(w_scale + n);
+      }
+  }
 #pragma unroll
   for (int i = 0; i < C::FM; ++i) {
     const int64_t m = m0 + wm * C::TM + i * 32 + (lane & 31);
@@ -420,8 +473,7 @@ __global__ __launch_bounds__(WM * WN * 64) void qgemm_dma(const int8_t* __restri
         if (VEC) {  // N % 4 == 0 and 16-byte aligned outputs: the four n are all in range
           if (ACC) *reinterpret_cast<v4i*>(ACC + m * N + n) = v4i{a[0], a[1], a[2], a[3]};
           if (Y) {
-            float4 sw = make_float4(sw0, sw0, sw0, sw0);
-            if (w_per_row) sw = *reinterpret_cast<const float4*>(w_scale + n);
+            const float4 sw = swv[j][g4];
             *reinterpret_cast<float4*>(Y + m * N + n) =
                 make_float4(((float)a[0] * sa) * sw.x, ((float)a[1] * sa) * sw.y,
                             ((float)a[2] * sa) * sw.z, ((float)a[3] * sa) * sw.w);
@@ -439,15 +491,15 @@ __global__ __launch_bounds__(WM * WN * 64) void qgemm_dma(const int8_t* __restri
   }
 }
 
-template <int BM, int BN, int WM, int WN, int NSTAGE, bool W4>
+template <int BM, int BN, int WM, int WN, int NSTAGE, bool W4, int KB = 128, int MINW = 1>
 static int launch_dma(const int8_t* a_q, const void* w_q, int64_t M, int64_t N, int64_t K,
                       const float* a_scale, const float* w_scale, int per_row, float* y_out,
                       int32_t* acc_out, hipStream_t st) {
-  using C = DmaCfg<BM, BN, WM, WN, NSTAGE, W4>;
+  using C = DmaCfg<BM, BN, WM, WN, NSTAGE, W4, KB>;
   // float4 / int4 stores need every 4-group of n inside the row and 16-byte aligned
   const bool vec = (N & 3) == 0 && (!y_out || aligned16(y_out)) && (!acc_out || aligned16(acc_out)) &&
                    (!(y_out && per_row) || aligned16(w_scale));
-  auto kern = vec ? qgemm_dma<BM, BN, WM, WN, NSTAGE, W4, true> : qgemm_dma<BM, BN, WM, WN, NSTAGE, W4, false>;
+  auto kern = vec ? qgemm_dma<BM, BN, WM, WN, NSTAGE, W4, true, KB, MINW> : qgemm_dma<BM, BN, WM, WN, NSTAGE, W4, false, KB, MINW>;
   static bool attr_set[2] = {false, false};  // dynamic LDS above 64 KiB has to be allowed once per kernel
   if (!attr_set[vec]) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -497,20 +549,22 @@ extern "C" int mpq_qgemm(const int8_t* a_q, const void* w_q, int w_storage_bits,
 #define MPQ_LAUNCH(W4_, FAST_) \
   qgemm_k<W4_, FAST_><<<grid, kGemmThreads, 0, st>>>(a_q, w_q, M, N, K, a_scale, w_scale, per_row, y_out, acc_out)
   if (fast) {
-    // tile choice: the largest tile that still gives every CU a block (tiles >= number of CUs)
-    // and does not pad N by more than its own width; small problems take the 64 x 64 tile.
+    // tile choice (from sweeps over the configured shapes): 256 x 256 when that still gives every
+    // CU a tile, 128 x 128 when it gives at least half of them one, else 64 x 64; three stages
+    // where k is long enough to keep them busy and the tile count is small (one workgroup per CU
+    // anyway), two otherwise (two workgroups per CU).
     auto tiles = [&](int64_t bm, int64_t bn) { return ((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
     int pick = 64;
     if (N > 128 && tiles(256, 256) >= kNumCU) pick = 256;
-    else if (N > 64 && tiles(128, 128) >= kNumCU) pick = 128;
+    else if (N > 64 && tiles(128, 128) >= kNumCU / 2) pick = 128;
 #define MPQ_DMA(BM_, BN_, WM_, WN_, NS_)                                                              \
   (w4 ? launch_dma<BM_, BN_, WM_, WN_, NS_, true>(a_q, w_q, M, N, K, a_scale, w_scale, per_row, y_out, \
                                                   acc_out, st)                                        \
       : launch_dma<BM_, BN_, WM_, WN_, NS_, false>(a_q, w_q, M, N, K, a_scale, w_scale, per_row,     \
                                                    y_out, acc_out, st))
     if (pick == 256) return MPQ_DMA(256, 256, 4, 2, 2);
-    if (pick == 128) return MPQ_DMA(128, 128, 4, 2, 2);
-    return MPQ_DMA(64, 64, 2, 2, 2);
+    if (pick == 128) return K >= 2048 ? MPQ_DMA(128, 128, 4, 2, 3) : MPQ_DMA(128, 128, 4, 2, 2);
+    return K >= 1024 ? MPQ_DMA(64, 64, 2, 2, 3) : MPQ_DMA(64, 64, 2, 2, 2);
 #undef MPQ_DMA
   }
   if (w4) { if (fast) MPQ_LAUNCH(true, true); else MPQ_LAUNCH(true, false); }

@@ -149,6 +149,52 @@ __global__ __launch_bounds__(kBlock) void qe_rows(const float* __restrict__ x, i
   }
 }
 
+// ---- per row, short rows: LPR lanes per row (16 or 64), 64 / LPR rows per wave ---------------------
+// The 2 NB per-row constants cost a division each; here lane j of a row group computes constant j
+// only and the group shares them through the cross-lane network, and the final sums need 4 DPP
+// steps instead of a full wave reduction.  cols % 4 == 0, x 16-byte aligned, cols <= kSeg.
+template <int NB, int LPR>
+__global__ __launch_bounds__(kBlock) void qe_rows_sub(const float* __restrict__ x, int64_t rows,
+                                                      int64_t cols, const float* __restrict__ absmax,
+                                                      int b_lo, double* __restrict__ out) {
+  constexpr int RW = kWave / LPR;  // rows per wave
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int lr = lane % LPR;
+  int64_t r = ((int64_t)blockIdx.x * (kBlock / kWave) + wave) * RW + lane / LPR;
+  const bool live = r < rows;
+  if (!live) r = rows - 1;  // keep every lane active for the cross-lane steps; result discarded
+  const float m = absmax[r];
+  // lane j < 7: inv of bit-width b_lo + j; lane 7 + j: scale of bit-width b_lo + j
+  float mine = 0.0f;
+  {
+    const int j = lr < 7 ? lr : lr - 7;
+    float sc, inv;
+    bit_constants(m, b_lo + (j < NB ? j : 0), sc, inv);
+    mine = lr < 7 ? inv : sc;
+  }
+  Sweep<NB> s;
+  s.m = m;
+#pragma unroll
+  for (int b = 0; b < NB; ++b) {
+    s.inv[b] = __shfl(mine, b, LPR);
+    s.sc[b] = __shfl(mine, 7 + b, LPR);
+    s.acc[b] = 0.0f;
+  }
+  const float4* r4 = reinterpret_cast<const float4*>(x + r * cols);
+  const int64_t e4 = cols >> 2;
+  int64_t i = lr;
+  for (; i + 3 * LPR < e4; i += 4 * LPR) {
+    const float4 a = r4[i], b = r4[i + LPR], c = r4[i + 2 * LPR], d = r4[i + 3 * LPR];
+    s.add4(a); s.add4(b); s.add4(c); s.add4(d);
+  }
+  for (; i < e4; i += LPR) s.add4(r4[i]);
+#pragma unroll
+  for (int b = 0; b < NB; ++b) {
+    const float w = LPR == 16 ? row16_sum(s.acc[b]) : wave_sum(s.acc[b]);
+    if (lr == 0 && live) out[r * NB + b] = (double)w;
+  }
+}
+
 // ---- per column: a lane owns CPL adjacent columns; the block's 4 waves take interleaved rows ----
 // partials: double [gridDim.y][cols][NB]
 template <int NB, int CPL>
@@ -277,7 +323,16 @@ static void launch_qe(const QeGeom& g, const float* x, int64_t rows, int64_t col
     qe_finish_tree<NB><<<1, kBlock, 0, st>>>(ws, (int64_t)g.gx, out);
   } else if (gran == MPQ_PER_ROW) {
     double* dst = g.nseg == 1 ? out : ws;
-    if (g.vec) qe_rows<NB, true><<<g.gx, kBlock, 0, st>>>(x, rows, cols, g.nseg, absmax, b_lo, dst);
+    if (g.vec && g.nseg == 1) {
+      // 16 lanes per row up to 2048 columns (>= 4 vectors per lane from 256 columns on), else a wave
+      if (cols <= 2048) {
+        const int64_t blocks = (rows + 15) / 16;
+        qe_rows_sub<NB, 16><<<(unsigned)blocks, kBlock, 0, st>>>(x, rows, cols, absmax, b_lo, out);
+      } else {
+        const int64_t blocks = (rows + 3) / 4;
+        qe_rows_sub<NB, 64><<<(unsigned)blocks, kBlock, 0, st>>>(x, rows, cols, absmax, b_lo, out);
+      }
+    } else if (g.vec) qe_rows<NB, true><<<g.gx, kBlock, 0, st>>>(x, rows, cols, g.nseg, absmax, b_lo, dst);
     else qe_rows<NB, false><<<g.gx, kBlock, 0, st>>>(x, rows, cols, g.nseg, absmax, b_lo, dst);
     if (g.nseg > 1) {
       const int64_t k = rows * NB;

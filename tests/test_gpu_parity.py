@@ -244,7 +244,8 @@ def test_qgemm_packed_int4_weights_bit_exact(mnk):
 
 
 @pytest.mark.parametrize("mnk,wbits", [((4096, 4096, 256), 8), ((4100, 4092, 160), 4), ((2048, 2048, 384), 8),
-                                        ((2085, 2047, 96), 4), ((2085, 2046, 112), 8), ((16384, 1024, 4096), 8)])
+                                        ((2085, 2047, 96), 4), ((2085, 2046, 112), 8), ((16384, 1024, 4096), 8),
+                                        ((1568, 2048, 2048), 4), ((1568, 512, 4608), 8), ((300, 200, 1152), 4)])
 def test_qgemm_large_tiles_on_sampled_rows(mnk, wbits):
     """Shapes that select the 128 x 128 and 256 x 256 tiles (ragged edges, N not a multiple of 4);
     rows of the product are independent, so the oracle checks a sample of rows exactly."""
