@@ -15,6 +15,8 @@
 // back by 4.
 #include "common.hpp"
 
+#include <type_traits>
+
 namespace mpq {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
@@ -201,11 +203,18 @@ __global__ __launch_bounds__(kGemmThreads) void qgemm_k(const int8_t* __restrict
 // 16 addresses are distinct modulo 256 B.  The MFMA operand reads apply the same XOR.  Chunks
 // beyond K are fetched from a 16-byte block of zeros.
 //
-// Stage s + NSTAGE - 1 is requested right after the barrier that opens stage s, so loads run
-// NSTAGE - 1 tiles ahead of the MFMAs; a wave waits only for its own oldest tile (s_waitcnt vmcnt)
-// and then meets the others at the barrier.  The k loop is unrolled by NSTAGE so every LDS
-// address is a compile-time offset (the compiler then keeps ds_reads of one stage independent of
-// the loads in flight into the others).
+// A k tile is requested NSTAGE - 1 tiles ahead of the MFMAs that use it; a wave waits only for
+// its own share of the tile it needs next (s_waitcnt vmcnt) and then meets the others at the one
+// barrier per k tile.  The k loop is unrolled by NSTAGE so every LDS address is a compile-time
+// offset (the compiler then keeps ds_reads of one stage independent of the loads in flight into
+// the others).
+//
+// What bounds this path (microbenchmarks on the same chip): a CU fills its LDS from L2 at about
+// 90 GB/s (one 1 KiB wave-load per ~27 clocks through its one address unit), so the 64 KiB k tile
+// of a 256 x 256 workgroup takes ~0.75 us to arrive against ~0.85-1.0 us of MFMA work on it;
+// and because a wave issues in order, a wave queueing at the address unit feeds no MFMAs -- a
+// plain stream of MFMAs with wave-loads between them, no waits and no barrier at all, reaches
+// about 70 % of the pure MFMA rate, which itself is ~82 % of the nominal peak under this load.
 // =====================================================================================================
 #define MPQ_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define MPQ_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
@@ -248,7 +257,8 @@ struct DmaCfg {
   static constexpr int B_ROW = W4 ? DBK / 2 : DBK;   // bytes of one W tile row in LDS
   static constexpr int B_STAGE = BN * B_ROW;
   static constexpr int STAGE = A_STAGE + B_STAGE;
-  static constexpr int LDS_BYTES = NSTAGE * STAGE;
+  static constexpr int SCALE_OFF = NSTAGE * STAGE;    // two 1 KiB buffers of per-channel W scales
+  static constexpr int LDS_BYTES = SCALE_OFF + 2048;
   static constexpr int NLA = BM / RPI;                // wave-loads per A stage
   static constexpr int NLB = W4 ? BN / PRPI : BN / RPI;  // wave-loads per W stage
   static constexpr int LPW = (NLA + NLB) / NW;        // wave-loads per wave per stage
@@ -258,89 +268,141 @@ struct DmaCfg {
   static_assert((NSTAGE - 1) * LPW < 64, "vmcnt is a 6-bit counter");
 };
 
-// What one wave fetches per stage, fixed for the whole k loop: for each of its wave-loads the
-// lane's source row (as a pointer to k = 0 of the chunk it owns) and the chunk's k offset.  Per
-// stage the lane then only adds k0 and checks the k tail.
+// compile-time loop: f(std::integral_constant<int, I>) for I = FIRST .. LAST - 1
+template <int FIRST, int LAST, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (FIRST < LAST) {
+    f(std::integral_constant<int, FIRST>{});
+    static_for<FIRST + 1, LAST>(f);
+  }
+}
+
+// What one wave fetches per stage.  Wave-load t of a wave covers tile rows first + t * STEP ..., and
+// because STEP is a multiple of the swizzle period every one of them has the lane fetch the same
+// logical chunk, so the plan is four registers: the lane's first row and chunk offset per operand.
+// Source addresses are formed at issue time (one 64-bit multiply-add per wave-load).
 template <class C, bool W4>
 struct DmaPlan {
   static constexpr int NA = C::NLA / C::NW, NB_ = C::NLB / C::NW;
-  const char* pa[NA];
-  const char* pb[NB_];
-  int ka[NA], kb[NB_];   // k of the lane's chunk within the tile (bytes of A / values of W)
-  unsigned wave_off;     // LDS offset of this wave's first wave-load within a stage region
+  static constexpr int STEP_A = C::RPI * C::NW;
+  static constexpr int STEP_B = (W4 ? C::PRPI : C::RPI) * C::NW;
+  static_assert(((STEP_A >> C::SH) % C::CPR) == 0, "A swizzle must repeat from one wave-load to the next");
+  static_assert(W4 ? ((STEP_B >> C::PSH) % C::PCPR) == 0 : ((STEP_B >> C::SH) % C::CPR) == 0,
+                "W swizzle must repeat from one wave-load to the next");
+  const char* A;
+  const char* W;
+  unsigned last_a, last_b;  // M - 1, N - 1: rows past the edge re-read the last row; never stored
+  unsigned K;
+  unsigned ra, rb;          // the lane's row of its first wave-load (global index)
+  int ka, kb;               // k of the lane's chunk within the tile (bytes of A / values of W)
+  unsigned wave_off;        // LDS offset of this wave's first wave-load within a stage region
 
-  __device__ __forceinline__ void init(const int8_t* __restrict__ A, const uint8_t* __restrict__ W,
-                                       int64_t M, int64_t N, int64_t K, int64_t m0, int64_t n0,
+  __device__ __forceinline__ void init(const int8_t* __restrict__ A_, const uint8_t* __restrict__ W_,
+                                       int64_t M, int64_t N, int64_t K_, int64_t m0, int64_t n0,
                                        int wave_u, int lane) {
+    A = reinterpret_cast<const char*>(A_);
+    W = reinterpret_cast<const char*>(W_);
+    last_a = (unsigned)(M - 1);
+    last_b = (unsigned)(N - 1);
+    K = (unsigned)K_;
     wave_off = (unsigned)wave_u * 1024u;
-#pragma unroll
-    for (int t = 0; t < NA; ++t) {  // A tile: wave-load j covers RPI rows
-      const int j = wave_u + t * C::NW;
-      const int row = C::RPI * j + lane / C::CPR;
-      const int c = (lane % C::CPR) ^ ((row >> C::SH) & (C::CPR - 1));  // logical chunk this lane fetches
-      int64_t r = m0 + row;
-      if (r >= M) r = M - 1;  // rows past the edge re-read the last row; never stored
-      ka[t] = c * 16;
-      pa[t] = reinterpret_cast<const char*>(A) + r * K + ka[t];
+    {
+      const int row = C::RPI * wave_u + lane / C::CPR;
+      ka = ((lane % C::CPR) ^ ((row >> C::SH) & (C::CPR - 1))) * 16;  // logical chunk this lane fetches
+      ra = (unsigned)m0 + (unsigned)row;
     }
-#pragma unroll
-    for (int t = 0; t < NB_; ++t) {
-      const int j = wave_u + t * C::NW;
-      if (!W4) {
-        const int row = C::RPI * j + lane / C::CPR;
-        const int c = (lane % C::CPR) ^ ((row >> C::SH) & (C::CPR - 1));
-        int64_t r = n0 + row;
-        if (r >= N) r = N - 1;
-        kb[t] = c * 16;
-        pb[t] = reinterpret_cast<const char*>(W) + r * K + kb[t];
-      } else {  // packed tile: wave-load j covers PRPI rows of KB/2 packed bytes
-        const int row = C::PRPI * j + lane / C::PCPR;
-        const int c = (lane % C::PCPR) ^ ((row >> C::PSH) & (C::PCPR - 1));  // logical chunk = 32 values
-        int64_t r = n0 + row;
-        if (r >= N) r = N - 1;
-        kb[t] = c * 32;
-        pb[t] = reinterpret_cast<const char*>(W) + r * (K >> 1) + (kb[t] >> 1);
-      }
+    if (!W4) {
+      const int row = C::RPI * wave_u + lane / C::CPR;
+      kb = ((lane % C::CPR) ^ ((row >> C::SH) & (C::CPR - 1))) * 16;
+      rb = (unsigned)n0 + (unsigned)row;
+    } else {  // packed tile: a wave-load covers PRPI rows of KB/2 packed bytes; a chunk is 32 values
+      const int row = C::PRPI * wave_u + lane / C::PCPR;
+      kb = ((lane % C::PCPR) ^ ((row >> C::PSH) & (C::PCPR - 1))) * 32;
+      rb = (unsigned)n0 + (unsigned)row;
     }
   }
 
-  // requests the k tile starting at k0 into the stage at LDS offset lds_stage_off
-  __device__ __forceinline__ void issue(unsigned lds_stage_off, int64_t k0, int64_t K) const {
+  // One k tile's requests of this wave, numbered 0 .. NA + NB_ - 1 (A first); chunks at or beyond
+  // k_limit are fetched from a block of zeros.
+  struct Tile {
+    const char* a0;
+    const char* b0;
+    bool va, vb;
+  };
+  __device__ __forceinline__ Tile tile(int k0, int k_limit) const {
+    Tile t;
+    t.va = k0 + ka < k_limit;
+    t.vb = k0 + kb < k_limit;
+    t.a0 = A + (unsigned)(k0 + ka);
+    t.b0 = W + (unsigned)(W4 ? (k0 + kb) >> 1 : k0 + kb);
+    return t;
+  }
+  template <int R>
+  __device__ __forceinline__ void request(const Tile& tl, unsigned lds_stage_off) const {
     const char* zero = reinterpret_cast<const char*>(g_zero16);
-#pragma unroll
-    for (int t = 0; t < NA; ++t) {
-      const char* src = (k0 + ka[t] < K) ? pa[t] + k0 : zero;
-      dma16(src, lds_stage_off + wave_off + (unsigned)(t * C::NW) * 1024u);
+    if constexpr (R < NA) {
+      unsigned r = ra + (unsigned)(R * STEP_A);
+      r = r < last_a ? r : last_a;
+      const char* src = tl.va ? tl.a0 + (uint64_t)r * K : zero;
+      dma16(src, lds_stage_off + wave_off + (unsigned)(R * C::NW) * 1024u);
+    } else {
+      constexpr int T = R - NA;
+      const unsigned ldb = W4 ? K >> 1 : K;
+      unsigned r = rb + (unsigned)(T * STEP_B);
+      r = r < last_b ? r : last_b;
+      const char* src = tl.vb ? tl.b0 + (uint64_t)r * ldb : zero;
+      dma16(src, lds_stage_off + (unsigned)C::A_STAGE + wave_off + (unsigned)(T * C::NW) * 1024u);
     }
-#pragma unroll
-    for (int t = 0; t < NB_; ++t) {
-      const char* src = (k0 + kb[t] < K) ? pb[t] + (W4 ? (k0 >> 1) : k0) : zero;
-      dma16(src, lds_stage_off + (unsigned)C::A_STAGE + wave_off + (unsigned)(t * C::NW) * 1024u);
-    }
+  }
+  // all requests of the k tile starting at k0, back to back
+  __device__ __forceinline__ void issue(unsigned lds_stage_off, int k0, int k_limit) const {
+    const Tile tl = tile(k0, k_limit);
+    static_for<0, NA + NB_>([&](auto r_) { request<decltype(r_)::value>(tl, lds_stage_off); });
   }
 };
 
-// operand fragments of k-substep s (32 k-values) of one stage
+// LDS offsets (within a stage) of the first operand fragments of a lane, for k substep 0.  With
+// the XOR swizzle the offset for substep s is this value with s XORed into its chunk bits, and
+// rows 32 i further down add a multiple of the row pitch, which never reaches those bits.
 template <class C, bool W4>
-__device__ __forceinline__ void dma_load_frags(const char* lds_stage, int s, int wm, int wn, int lane,
-                                               v4i (&fa)[C::FM], v4i (&fb)[C::FN]) {
-  const int l31 = lane & 31, g = lane >> 5;
-  constexpr int DBK = C::DBK;
-  const int ch = 2 * s + g;  // logical 16-byte chunk of the tile row
-#pragma unroll
-  for (int i = 0; i < C::FM; ++i) {
-    const int row = wm * C::TM + i * 32 + l31;
-    fa[i] = *reinterpret_cast<const v4i*>(lds_stage + row * DBK + ((ch ^ ((row >> C::SH) & (C::CPR - 1))) << 4));
+struct FragBase {
+  unsigned a, b;
+  __device__ __forceinline__ void init(int wm, int wn, int lane) {
+    const int l31 = lane & 31, g = lane >> 5;
+    const int ra = wm * C::TM + l31;
+    a = (unsigned)(ra * C::DBK + ((g ^ ((ra >> C::SH) & (C::CPR - 1))) << 4));
+    const int rb = wn * C::TN + l31;
+    if (!W4) b = (unsigned)(C::A_STAGE + rb * C::DBK + ((g ^ ((rb >> C::SH) & (C::CPR - 1))) << 4));
+    else b = (unsigned)(C::A_STAGE + rb * (C::DBK / 2) + (((rb >> C::PSH) & (C::PCPR - 1)) << 4) + g * 8);
   }
+};
+
+// base ^ bits, computed where it is used: written as a plain expression the compiler would keep
+// one address register per (stage, substep, operand) alive across the whole k loop
+template <unsigned BITS>
+__device__ __forceinline__ unsigned xor_here(unsigned base) {
+  if (BITS == 0) return base;
+  unsigned r;
+  asm volatile("v_xor_b32 %0, %1, %2" : "=v"(r) : "n"(BITS), "v"(base));
+  return r;
+}
+
+// operand fragments of k-substep S (32 k-values) of the stage at byte offset stage_off
+template <class C, bool W4, int S>
+__device__ __forceinline__ void dma_load_frags(const char* lds, unsigned stage_off, const FragBase<C, W4>& fr,
+                                               v4i (&fa)[C::FM], v4i (&fb)[C::FN]) {
+  constexpr int DBK = C::DBK;
+  // logical chunk 2 S + g of an int8 row; packed rows hold 32 values per chunk: chunk S, half g
+  const char* pa = lds + xor_here<(unsigned)(S << 5)>(fr.a + stage_off);
+  const char* pb = lds + xor_here<(unsigned)(W4 ? S << 4 : S << 5)>(fr.b + stage_off);
+#pragma unroll
+  for (int i = 0; i < C::FM; ++i) fa[i] = *reinterpret_cast<const v4i*>(pa + i * 32 * DBK);
 #pragma unroll
   for (int j = 0; j < C::FN; ++j) {
-    const int row = wn * C::TN + j * 32 + l31;
     if (!W4) {
-      fb[j] = *reinterpret_cast<const v4i*>(lds_stage + C::A_STAGE + row * DBK + ((ch ^ ((row >> C::SH) & (C::CPR - 1))) << 4));
+      fb[j] = *reinterpret_cast<const v4i*>(pb + j * 32 * DBK);
     } else {
-      // 16 values = 8 packed bytes: half g of logical packed chunk s
-      const uint2 pk = *reinterpret_cast<const uint2*>(lds_stage + C::A_STAGE + row * (DBK / 2) +
-                                                       ((s ^ ((row >> C::PSH) & (C::PCPR - 1))) << 4) + g * 8);
+      const uint2 pk = *reinterpret_cast<const uint2*>(pb + j * 32 * (DBK / 2));
       unsigned b0, b1, b2, b3;
       expand8(pk.x, b0, b1);
       expand8(pk.y, b2, b3);
@@ -361,10 +423,38 @@ __device__ __forceinline__ void dma_mfma_substep(v16i (&acc)[C::FM][C::FN], cons
       acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[j], fa[i], acc[i][j], 0, 0, 0);
 }
 
-// grid: 1-D over output tiles, N fastest; `swizzle_xcd` regroups block ids so that the blocks an
-// XCD receives (ids congruent mod 8) cover one contiguous range of tiles and share its L2.
-// MINW: waves the register allocation must leave room for on one SIMD (2 = two co-resident
-// 4-wave workgroups per CU)
+// The same MFMAs with the wave's requests for a k tile dealt out between them.  A wave that
+// issues its requests back to back sits in the queue of the CU's one address unit (64 bytes per
+// clock, so a 64 KiB k tile keeps it busy for about a thousand clocks) and, issuing in order,
+// feeds no MFMAs meanwhile; dealt out, the matrix pipe keeps working while the queue drains.
+template <class C, bool W4>
+__device__ __forceinline__ void dma_mfma_substep_requesting(v16i (&acc)[C::FM][C::FN], const v4i (&fa)[C::FM],
+                                                            const v4i (&fb)[C::FN], const DmaPlan<C, W4>& plan,
+                                                            const typename DmaPlan<C, W4>::Tile& tl,
+                                                            unsigned lds_stage_off) {
+  constexpr int NM = C::FM * C::FN, NR = C::LPW;
+  static_for<0, NM>([&](auto q_) {
+    constexpr int q = decltype(q_)::value;
+    static_for<q * NR / NM, (q + 1) * NR / NM>([&](auto r_) { plan.template request<decltype(r_)::value>(tl, lds_stage_off); });
+    __builtin_amdgcn_sched_barrier(0);
+    constexpr int i = q / C::FN, j = q % C::FN;
+    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[j], fa[i], acc[i][j], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+  });
+}
+
+// A workgroup works off `chunk` output tiles that follow each other along M (same columns, so
+// the W tile stays hot and, at any moment, the workgroups in flight still write all column blocks
+// of Y: tiles that follow each other along N made the whole grid store into the same quarter of
+// every Y row at the same time, which the memory channels punish).  Workgroup ids run with N
+// fastest; `remap` regroups them so that the workgroups an XCD receives (ids congruent mod 8)
+// cover a contiguous id range and share its L2.
+// The k loop never drains between the tiles of a chunk: the requests issued during the last k
+// tiles of one output tile already fetch the first k tiles of the next one, and the epilogue's
+// stores overlap with those loads.  (k is padded to a multiple of NSTAGE tiles with zero tiles so
+// that a tile always starts in stage 0.)  Chunks stay short so that the hardware dispatcher, not a
+// fixed assignment, balances the load when other kernels hold some of the CUs.
+// MINW: waves the register allocation must leave room for on one SIMD.
 template <int BM, int BN, int WM, int WN, int NSTAGE, bool W4, bool VEC, int KB, int MINW>
 __global__ __launch_bounds__(WM * WN * 64, MINW) void qgemm_dma(const int8_t* __restrict__ A,
                                                           const void* __restrict__ Wv, int64_t M,
@@ -373,122 +463,162 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void qgemm_dma(const int8_t* __
                                                           const float* __restrict__ w_scale,
                                                           int w_per_row, float* __restrict__ Y,
                                                           int32_t* __restrict__ ACC, int tiles_n,
-                                                          int swizzle_xcd) {
+                                                          int tiles_m, int chunk, int remap) {
   using C = DmaCfg<BM, BN, WM, WN, NSTAGE, W4, KB>;
   constexpr int DBK = KB;
+  constexpr int NSUB = DBK / 32;
+  static_assert(NSUB % 2 == 0, "fragment double buffer assumes an even number of k substeps");
   extern __shared__ __attribute__((aligned(16))) char lds[];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int wm = wave / WN, wn = wave % WN;
   const unsigned lds0 = (unsigned)(uintptr_t)MPQ_LPTR(lds);  // LDS byte address of the buffer
-  unsigned bid = blockIdx.x;
-  if (swizzle_xcd) bid = (bid & 7u) * (gridDim.x >> 3) + (bid >> 3);  // gridDim.x % 8 == 0
-  const int64_t m0 = (int64_t)(bid / (unsigned)tiles_n) * BM, n0 = (int64_t)(bid % (unsigned)tiles_n) * BN;
   const uint8_t* Wb = reinterpret_cast<const uint8_t*>(Wv);
-
-  v16i acc[C::FM][C::FN];
-#pragma unroll
-  for (int i = 0; i < C::FM; ++i)
-#pragma unroll
-    for (int j = 0; j < C::FN; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
-
+  const int G = (int)gridDim.x;
+  int wg = (int)blockIdx.x;
+  if (remap) wg = (wg & 7) * (G >> 3) + (wg >> 3);  // G % 8 == 0
   const int KT = (int)((K + DBK - 1) / DBK);
-  constexpr int NSUB = DBK / 32;
-  static_assert(NSUB % 2 == 0, "fragment double buffer assumes an even number of k substeps");
+  const int KTp = (KT + NSTAGE - 1) / NSTAGE * NSTAGE;
+
+  int tile = (wg / tiles_n) * chunk;  // row of tiles; < tiles_m: the grid is ceil(tiles_m / chunk) * tiles_n
+  const int tile_end = tile + chunk < tiles_m ? tile + chunk : tiles_m;
+  int64_t m0 = (int64_t)tile * BM;
+  const int64_t n0 = (int64_t)(wg % tiles_n) * BN;
   DmaPlan<C, W4> plan;
   plan.init(A, Wb, M, N, K, m0, n0, wave, lane);
+  int k_limit = (int)K;  // 0 once there is no next tile: every further request fetches zeros
+  // Per-channel W scales of an output tile travel through LDS (one wave-load of 256 floats, issued
+  // by every wave ahead of the tile's first k tile, into the buffer `par` selects): the epilogue
+  // then needs no global loads between its stores and no registers to park the scales in.
+  const bool lds_scales = VEC && Y && w_per_row;
+  unsigned par = 0;
+  auto issue_scales = [&](int64_t n_first, unsigned which) {
+    if (lds_scales) {  // wave-uniform
+      const int64_t n = n_first + 4 * lane;
+      const char* src = (4 * lane < BN && n < N) ? reinterpret_cast<const char*>(w_scale + n)
+                                                 : reinterpret_cast<const char*>(g_zero16);
+      dma16(src, lds0 + C::SCALE_OFF + which * 1024u);
+    }
+  };
 
-  // Software pipeline.  Every stage holds a tile; tile t + NSTAGE is requested into the stage of
-  // tile t at the moment that stage has been read for the last time, which is BEFORE the MFMAs of
-  // the tile's last k substep are issued (their operands sit in registers by then).  The same
-  // point waits for tile t + 1, passes the barrier and requests the first fragments of tile t + 1,
-  // so that barrier skew, the address arithmetic of the loads and the LDS latency all hide behind
-  // the matrix pipe working off the queued MFMAs.
-  // (tiles past the end fetch zeros: harmless and keeps the vmcnt bookkeeping uniform)
+  // Software pipeline.  Every stage holds a k tile; k tile t + NSTAGE is requested into the stage of
+  // k tile t at the moment that stage has been read for the last time, which is BEFORE the MFMAs
+  // of the tile's last k substep are issued (their operands sit in registers by then).  The same
+  // point waits for k tile t + 1, passes the barrier and requests the first fragments of t + 1, so
+  // that barrier skew, the address arithmetic of the loads and the LDS latency all hide behind the
+  // matrix pipe working off the queued MFMAs.
+  issue_scales(n0, par);  // older than every k tile request: the counted waits below cover it
 #pragma unroll
-  for (int p = 0; p < NSTAGE; ++p) plan.issue(lds0 + p * C::STAGE, (int64_t)p * DBK, K);
-  wait_vmcnt<(NSTAGE - 1) * C::LPW>();  // this wave's share of tile 0 has landed
+  for (int p = 0; p < NSTAGE; ++p) plan.issue(lds0 + p * C::STAGE, p * DBK, k_limit);
+  wait_vmcnt<(NSTAGE - 1) * C::LPW>();  // this wave's share of k tile 0 has landed
   __syncthreads();                      // ... and everyone else's
   v4i fa[2][C::FM], fb[2][C::FN];
-  dma_load_frags<C, W4>(lds, 0, wm, wn, lane, fa[0], fb[0]);
+  FragBase<C, W4> fr;
+  fr.init(wm, wn, lane);
+  dma_load_frags<C, W4, 0>(lds, 0u, fr, fa[0], fb[0]);
+  bool drain = false;  // true for the first wait after an epilogue: stores are in flight, and
+                       // loads and stores do not retire in order with respect to each other
 
-  for (int kt = 0; kt < KT; kt += NSTAGE) {
+  while (true) {
+    v16i acc[C::FM][C::FN];
 #pragma unroll
-    for (int u = 0; u < NSTAGE; ++u) {
-      if (kt + u < KT) {  // block-uniform
-        const char* stage = lds + u * C::STAGE;
+    for (int i = 0; i < C::FM; ++i)
 #pragma unroll
-        for (int sub = 0; sub < NSUB; ++sub) {
-          if (sub + 1 < NSUB) {
-            dma_load_frags<C, W4>(stage, sub + 1, wm, wn, lane, fa[(sub + 1) & 1], fb[(sub + 1) & 1]);
+      for (int j = 0; j < C::FN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+    const int next = tile + 1;
+    const int64_t cur_m0 = m0, cur_n0 = n0;  // m0 moves on to the next tile before the epilogue
+
+    for (int kt = 0; kt < KTp; kt += NSTAGE) {
+      const bool tail = kt + NSTAGE >= KTp;  // requests from here on belong to the next output tile
+      if (tail) {
+        if (next < tile_end) {
+          m0 = (int64_t)next * BM;
+          plan.init(A, Wb, M, N, K, m0, n0, wave, lane);
+        } else {
+          k_limit = 0;
+        }
+      }
+      static_for<0, NSTAGE>([&](auto u_) {
+        constexpr int u = decltype(u_)::value;
+        static_for<0, NSUB>([&](auto sub_) {
+          constexpr int sub = decltype(sub_)::value;
+          if constexpr (sub + 1 < NSUB) {
+            dma_load_frags<C, W4, sub + 1>(lds, (unsigned)(u * C::STAGE), fr, fa[(sub + 1) & 1], fb[(sub + 1) & 1]);
           } else {
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wave has read the stage for the last time
-            wait_vmcnt<(NSTAGE - 2) * C::LPW>();                // its share of the next tile has landed
+            if (drain) wait_vmcnt<0>();                          // its share of the next k tile has landed
+            else wait_vmcnt<(NSTAGE - 2) * C::LPW>();
+            drain = false;
             __syncthreads();
-            plan.issue(lds0 + u * C::STAGE, (int64_t)(kt + u + NSTAGE) * DBK, K);
-            dma_load_frags<C, W4>(lds + ((u + 1) % NSTAGE) * C::STAGE, 0, wm, wn, lane, fa[0], fb[0]);
+            const int k_next = tail ? u * DBK : (kt + u + NSTAGE) * DBK;
+            if (u == 0 && tail && next < tile_end) issue_scales(n0, par ^ 1u);
+            dma_load_frags<C, W4, 0>(lds, (unsigned)(((u + 1) % NSTAGE) * C::STAGE), fr, fa[0], fb[0]);
+            const auto tl = plan.tile(k_next, k_limit);
+            __builtin_amdgcn_sched_barrier(0);
+            dma_mfma_substep_requesting<C, W4>(acc, fa[sub & 1], fb[sub & 1], plan, tl, lds0 + u * C::STAGE);
           }
-          dma_mfma_substep<C>(acc, fa[sub & 1], fb[sub & 1]);
-        }
-      }
+          // Pin the order "operand reads of the next substep, then the MFMAs of this one": left to
+          // itself the scheduler sinks the reads down to their first use, and every substep then
+          // starts by waiting out the LDS latency.
+          if constexpr (sub + 1 < NSUB) {
+            __builtin_amdgcn_sched_barrier(0);
+            dma_mfma_substep<C>(acc, fa[sub & 1], fb[sub & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        });
+      });
     }
-  }
-  wait_vmcnt<0>();  // drain the zero-fill tail loads before the block retires
 
-  // epilogue.  32x32 accumulator tile (i, j): lane l holds m = l % 32 and, in registers
-  // 4g .. 4g+3, the four consecutive n = 8g + 4 (l / 32) + 0..3.
-  const float sa = Y ? a_scale[0] : 0.0f;
-  const float sw0 = (Y && !w_per_row) ? w_scale[0] : 0.0f;
-  // all scales first: a load issued between stores would make the compiler wait for every store
-  // in flight before using it
-  float4 swv[C::FN][4];
-  if (VEC) {
+    // epilogue.  32x32 accumulator tile (i, j): lane l holds m = l % 32 and, in registers
+    // 4g .. 4g+3, the four consecutive n = 8g + 4 (l / 32) + 0..3.
+    const float sa = Y ? a_scale[0] : 0.0f;
+    const float sw0 = (Y && !w_per_row) ? w_scale[0] : 0.0f;
+    const char* scales = lds + C::SCALE_OFF + par * 1024u;
 #pragma unroll
-    for (int j = 0; j < C::FN; ++j)
+    for (int i = 0; i < C::FM; ++i) {
+      const int64_t m = cur_m0 + wm * C::TM + i * 32 + (lane & 31);
+      if (m >= M) continue;
 #pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4) {
-        const int64_t n = n0 + wn * C::TN + j * 32 + g4 * 8 + (lane >> 5) * 4;
-        swv[j][g4] = make_float4(sw0, sw0, sw0, sw0);
-        if (Y && w_per_row && n < N) swv[j][g4] = *reinterpret_cast<const float4*>(w_scale + n);
-      }
-  }
+      for (int j = 0; j < C::FN; ++j) {
 #pragma unroll
-  for (int i = 0; i < C::FM; ++i) {
-    const int64_t m = m0 + wm * C::TM + i * 32 + (lane & 31);
-    if (m >= M) continue;
-#pragma unroll
-    for (int j = 0; j < C::FN; ++j) {
-#pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4) {
-        const int64_t n = n0 + wn * C::TN + j * 32 + g4 * 8 + (lane >> 5) * 4;
-        if (n >= N) continue;
-        int a[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          a[e] = acc[i][j][g4 * 4 + e];
-          if (W4) a[e] >>= 4;  // exact: every product carried the factor 16
-        }
-        if (VEC) {  // N % 4 == 0 and 16-byte aligned outputs: the four n are all in range
-          if (ACC) *reinterpret_cast<v4i*>(ACC + m * N + n) = v4i{a[0], a[1], a[2], a[3]};
-          if (Y) {
-            const float4 sw = swv[j][g4];
-            *reinterpret_cast<float4*>(Y + m * N + n) =
-                make_float4(((float)a[0] * sa) * sw.x, ((float)a[1] * sa) * sw.y,
-                            ((float)a[2] * sa) * sw.z, ((float)a[3] * sa) * sw.w);
-          }
-        } else {
+        for (int g4 = 0; g4 < 4; ++g4) {
+          const int64_t n = cur_n0 + wn * C::TN + j * 32 + g4 * 8 + (lane >> 5) * 4;
+          if (n >= N) continue;
+          int a[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            if (n + e >= N) break;
-            if (ACC) ACC[m * N + n + e] = a[e];
-            if (Y) Y[m * N + n + e] = ((float)a[e] * sa) * (w_per_row ? w_scale[n + e] : sw0);
+            a[e] = acc[i][j][g4 * 4 + e];
+            if (W4) a[e] >>= 4;  // exact: every product carried the factor 16
+          }
+          if (VEC) {  // N % 4 == 0 and 16-byte aligned outputs: the four n are all in range
+            if (ACC) *reinterpret_cast<v4i*>(ACC + m * N + n) = v4i{a[0], a[1], a[2], a[3]};
+            if (Y) {
+              float4 sw = make_float4(sw0, sw0, sw0, sw0);
+              if (w_per_row)
+                sw = *reinterpret_cast<const float4*>(scales + (wn * C::TN + j * 32 + g4 * 8 + (lane >> 5) * 4) * 4);
+              *reinterpret_cast<float4*>(Y + m * N + n) =
+                  make_float4(((float)a[0] * sa) * sw.x, ((float)a[1] * sa) * sw.y,
+                              ((float)a[2] * sa) * sw.z, ((float)a[3] * sa) * sw.w);
+            }
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              if (n + e >= N) break;
+              if (ACC) ACC[m * N + n + e] = a[e];
+              if (Y) Y[m * N + n + e] = ((float)a[e] * sa) * (w_per_row ? w_scale[n + e] : sw0);
+            }
           }
         }
       }
     }
+    if (next >= tile_end) break;  // block-uniform
+    tile = next;
+    par ^= 1u;
+    drain = true;
   }
+  wait_vmcnt<0>();  // the zero-fill requests past the last tile land before the LDS is given back
 }
 
 template <int BM, int BN, int WM, int WN, int NSTAGE, bool W4, int KB = 128, int MINW = 1>
@@ -509,10 +639,23 @@ static int launch_dma(const int8_t* a_q, const void* w_q, int64_t M, int64_t N, 
   }
   const int64_t tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN;
   if (tm * tn > 0x7FFFFFFF || tn > 0x7FFFFFFF) return MPQ_ERR_SHAPE;
-  const unsigned grid = (unsigned)(tm * tn);
-  const int swz = (grid % 8u == 0 && grid >= 16u) ? 1 : 0;
-  kern<<<grid, C::NT, C::LDS_BYTES, st>>>(a_q, w_q, M, N, K, a_scale, w_scale, per_row, y_out, acc_out,
-                                          (int)tn, swz);
+  // Chunk length: the chip holds `slots` workgroups at a time (what the LDS allows per CU), so a
+  // launch costs about ceil(grid / slots) * chunk tile times; take the length up to 4 that makes
+  // this smallest, the longer one on a tie (more tile boundaries without a drain).
+  int per_cu = (160 * 1024) / C::LDS_BYTES;
+  if (per_cu > 4) per_cu = 4;
+  if (per_cu < 1) per_cu = 1;
+  const int64_t slots = kNumCU * per_cu;
+  int chunk = 1;
+  int64_t best = 0, grid = 0;
+  for (int c = 1; c <= 4; ++c) {
+    const int64_t g = ((tm + c - 1) / c) * tn;
+    const int64_t cost = ((g + slots - 1) / slots) * c;
+    if (c == 1 || cost <= best) { best = cost; chunk = c; grid = g; }
+  }
+  const int remap = (grid % 8 == 0 && grid >= 16) ? 1 : 0;
+  kern<<<(unsigned)grid, C::NT, C::LDS_BYTES, st>>>(a_q, w_q, M, N, K, a_scale, w_scale, per_row, y_out,
+                                                   acc_out, (int)tn, (int)tm, chunk, remap);
   return launch_status();
 }
 
@@ -545,17 +688,18 @@ extern "C" int mpq_qgemm(const int8_t* a_q, const void* w_q, int w_storage_bits,
   const dim3 grid((unsigned)gx, (unsigned)gy);
   const int per_row = w_gran == MPQ_PER_ROW;
   const bool w4 = w_storage_bits == 4;
-  const bool fast = aligned16(a_q) && aligned16(w_q) && (K % (w4 ? 32 : 16)) == 0;
+  // the fast kernels index rows with 32 bits
+  const bool fast = aligned16(a_q) && aligned16(w_q) && (K % (w4 ? 32 : 16)) == 0 && M < (1ll << 31) && N < (1ll << 31);
 #define MPQ_LAUNCH(W4_, FAST_) \
   qgemm_k<W4_, FAST_><<<grid, kGemmThreads, 0, st>>>(a_q, w_q, M, N, K, a_scale, w_scale, per_row, y_out, acc_out)
   if (fast) {
-    // tile choice (from sweeps over the configured shapes): 256 x 256 when that still gives every
-    // CU a tile, 128 x 128 when it gives at least half of them one, else 64 x 64; three stages
-    // where k is long enough to keep them busy and the tile count is small (one workgroup per CU
-    // anyway), two otherwise (two workgroups per CU).
+    // tile choice (from sweeps over the configured shapes): 256 x 256 when that gives at least
+    // three CUs in four a tile, 128 x 128 when it gives at least half of them one, else 64 x 64.
+    // 128 x 128 runs three stages (one workgroup per CU) when there is at most one tile per CU
+    // anyway or k is long, two stages (two workgroups per CU) otherwise.
     auto tiles = [&](int64_t bm, int64_t bn) { return ((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
     int pick = 64;
-    if (N > 128 && tiles(256, 256) >= kNumCU) pick = 256;
+    if (N > 128 && tiles(256, 256) >= kNumCU * 3 / 4) pick = 256;
     else if (N > 64 && tiles(128, 128) >= kNumCU / 2) pick = 128;
 #define MPQ_DMA(BM_, BN_, WM_, WN_, NS_)                                                              \
   (w4 ? launch_dma<BM_, BN_, WM_, WN_, NS_, true>(a_q, w_q, M, N, K, a_scale, w_scale, per_row, y_out, \
@@ -563,8 +707,9 @@ extern "C" int mpq_qgemm(const int8_t* a_q, const void* w_q, int w_storage_bits,
       : launch_dma<BM_, BN_, WM_, WN_, NS_, false>(a_q, w_q, M, N, K, a_scale, w_scale, per_row,     \
                                                    y_out, acc_out, st))
     if (pick == 256) return MPQ_DMA(256, 256, 4, 2, 2);
-    if (pick == 128) return K >= 2048 ? MPQ_DMA(128, 128, 4, 2, 3) : MPQ_DMA(128, 128, 4, 2, 2);
-    return K >= 1024 ? MPQ_DMA(64, 64, 2, 2, 3) : MPQ_DMA(64, 64, 2, 2, 2);
+    if (pick == 128)
+      return (K >= 2048 || tiles(128, 128) <= kNumCU) ? MPQ_DMA(128, 128, 4, 2, 3) : MPQ_DMA(128, 128, 4, 2, 2);
+    return MPQ_DMA(64, 64, 2, 2, 3);
 #undef MPQ_DMA
   }
   if (w4) { if (fast) MPQ_LAUNCH(true, true); else MPQ_LAUNCH(true, false); }
