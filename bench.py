@@ -14,7 +14,8 @@ Other workloads (the parity-test configurations, measured with the same machiner
     cfg3  BERT-base encoder linears at M = 12288, same per-layer path, per-tensor scales
     cfg4  sensitivity sweep over the 96 BERT-large weight tensors: absmax + quant_error per tensor
           and per output channel, noise at every b = 2..8
-    cfg5  64 candidate bit configurations of a BERT-large FFN block at M = 16384, back to back
+    cfg5  64 candidate bit configurations of a BERT-large FFN block at M = 16384, back to back,
+          the output score taken in the second GEMM's epilogue (cfg5-unfused: qgemm + sse_pair)
 All inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 """
 from __future__ import annotations
@@ -344,7 +345,7 @@ def workload_cfg4(torch, P, workloads):
 
 # ------------------------------------------------------------------------------------------------
 # configuration 5: candidate scoring on a BERT-large FFN block
-def workload_cfg5(torch, P, workloads):
+def workload_cfg5(torch, P, workloads, fused):
     x, w1, w2 = workloads.cfg5_tensors()
     cands = workloads.cfg5_candidates()
     dx, dw1, dw2 = torch.from_numpy(x).cuda(), torch.from_numpy(w1).cuda(), torch.from_numpy(w2).cuda()
@@ -396,20 +397,25 @@ def workload_cfg5(torch, P, workloads):
             with rec("fake_quant", 5 * g.numel()):
                 P.fake_quant(g, am_h, ba2, want_y=False, codes=ch)
             P.scale_from_absmax(am_h, ba2, out=s[3])
-            with rec("qgemm", M * N1 + N2 * N1 * st2 // 8 + 4 * M * N2, 2 * M * N2 * N1):
-                P.qgemm(ch, q2, s[3], s[1], st2, y=y, ws=ws)
-            with rec("sse_pair", 8 * y.numel()):
-                P.sse_pair(y, y_ref, out=scores[c:c + 1], ws=ws)
+            if fused:  # the score is taken in the epilogue: Y_ref is read, Y is never written
+                with rec("qgemm", M * N1 + N2 * N1 * st2 // 8 + 4 * M * N2, 2 * M * N2 * N1):
+                    P.qgemm_score(ch, q2, s[3], s[1], y_ref, st2, out=scores[c:c + 1], ws=ws)
+            else:
+                with rec("qgemm", M * N1 + N2 * N1 * st2 // 8 + 4 * M * N2, 2 * M * N2 * N1):
+                    P.qgemm(ch, q2, s[3], s[1], st2, y=y, ws=ws)
+                with rec("sse_pair", 8 * y.numel()):
+                    P.sse_pair(y, y_ref, out=scores[c:c + 1], ws=ws)
 
     def snapshot():
         return [scores.clone()]
 
     per_cand = (4.75 * (dw1.numel() + dw2.numel()) + 5 * dx.numel() + (M * K1 + N1 * K1 + 4 * M * N1)
-                + 4 * M * N1 + 5 * M * N1 + (M * N1 + N2 * N1 + 4 * M * N2) + 8 * M * N2)
+                + 4 * M * N1 + 5 * M * N1 + (M * N1 + N2 * N1 + 4 * M * N2) + (0 if fused else 8 * M * N2))
     nbytes = int(len(cands) * per_cand + 4 * (dx.numel() + dw1.numel() + dw2.numel()))
     ops = len(cands) * (2 * M * N1 * K1 + 2 * M * N2 * N1)
     label = ("cfg5: 64 candidate bit configurations of a BERT-large FFN block (1024 -> 4096 -> 1024) at "
-             "M = 16384, back to back: re-quantize, qgemm, GELU (torch), re-quantize, qgemm, output SSE")
+             "M = 16384, back to back: re-quantize, qgemm, GELU (torch), re-quantize, qgemm, output SSE"
+             + (" taken in the second GEMM's epilogue" if fused else " in a pass of its own"))
     return step, snapshot, nbytes, ops, label, len(cands)
 
 
@@ -461,7 +467,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", choices=["cfg2", "cfg3", "cfg4", "cfg5"], default="cfg2")
+    ap.add_argument("--workload", choices=["cfg2", "cfg3", "cfg4", "cfg5", "cfg5-unfused"], default="cfg2")
     ap.add_argument("--cpu-sample-rows", type=int, default=1024)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -491,7 +497,7 @@ def main():
     elif args.workload == "cfg4":
         step, snapshot, nbytes, ops, label = workload_cfg4(torch, mpq, workloads)
     else:
-        step, snapshot, nbytes, ops, label, ncand = workload_cfg5(torch, mpq, workloads)
+        step, snapshot, nbytes, ops, label, ncand = workload_cfg5(torch, mpq, workloads, args.workload == "cfg5")
         extra["candidates_per_step"] = ncand
         args.steps = min(args.steps, 5)   # one step is 64 candidates (~20 ms); keep the GPU time bounded
     torch.cuda.synchronize()

@@ -134,6 +134,47 @@ size_t mpq_sse_pair_workspace_bytes(int64_t n);
 int mpq_sse_pair(const float* y, const float* y_ref, int64_t n, double* sse_out, void* ws,
                  size_t ws_bytes, void* stream);
 
+/* ---- "Evaluate f(x, w) and save accuracy a" of Alg. 1 / Alg. 2 in one call -------------------
+ * The layer of mpq_qgemm with the score of mpq_sse_pair taken in its epilogue:
+ * sse_out[0] = sum_{m,n} (y[m][n] - y_ref[m][n])^2 (double), y exactly as mpq_qgemm defines it.
+ * y_ref      fp32 [M x N], required.
+ * y_out      nullable: when NULL the layer output is never written, which is what a search over
+ *            bit configurations wants for the last layer (only the score leaves the chip).
+ * Workspace: one double per workgroup, size from the query; needs no initialisation.
+ * fp32 per-lane partials (at most a few hundred terms each), fixed-order double combine:
+ * results are reproducible from call to call.  Other arguments and errors as mpq_qgemm. */
+size_t mpq_qgemm_score_workspace_bytes(int64_t M, int64_t N, int64_t K, int w_storage_bits);
+int mpq_qgemm_score(const int8_t* a_q, const void* w_q, int w_storage_bits, int64_t M, int64_t N,
+                    int64_t K, const float* a_scale, const float* w_scale, int w_gran,
+                    const float* y_ref, double* sse_out, float* y_out, void* ws, size_t ws_bytes,
+                    void* stream);
+
+/* ---- Alg. 1 (bisection search) and Alg. 2 (greedy search): host code ---------------------------
+ * Both decide which per-layer bit configuration to evaluate next and return the final one; they
+ * launch nothing themselves.  All pointers here are HOST pointers.
+ * eval       "Evaluate f(x, lw) and save accuracy a": called with bits[n_layers] (bits[l] = width
+ *            of layer l) and `user`; returns the accuracy a, which is compared with `target`
+ *            (a >= target meets it).  Called from the calling thread, one call at a time.
+ * order      the layer ids 0 .. n_layers-1 sorted by sensitivity in ascending order (a
+ *            permutation, else MPQ_ERR_SHAPE).
+ * bit_widths the available widths bs, visited in the order given (pass them descending: highest
+ *            quantized precision first); each in 2..16, else MPQ_ERR_BITS.  The working
+ *            configuration starts at the largest of them.
+ * flags      0, or MPQ_SEARCH_ENSURE_TARGET (bisection only): if the loop of Alg. 1 stops on an
+ *            evaluation that missed the target, fall back to the largest layer count that met it
+ *            instead of keeping the failed one, as the printed arithmetic would.
+ * config_out [n_layers] final width per layer.  n_evals_out nullable: number of eval calls.
+ * Threshold arithmetic of Alg. 1: integers, floor division, stop when an update leaves thr
+ * unchanged. */
+typedef double (*mpq_eval_fn)(const int* bits, int n_layers, void* user);
+enum mpq_search_flags { MPQ_SEARCH_ENSURE_TARGET = 1 };
+int mpq_search_bisection(const int* order, int n_layers, const int* bit_widths, int n_bits,
+                         double target, int flags, mpq_eval_fn eval, void* user, int* config_out,
+                         int* n_evals_out);
+int mpq_search_greedy(const int* order, int n_layers, const int* bit_widths, int n_bits,
+                      double target, int flags, mpq_eval_fn eval, void* user, int* config_out,
+                      int* n_evals_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -110,14 +110,16 @@ __device__ __forceinline__ void store4(int8_t* lds, const Stage4& s) {
 
 // ---- the kernel ---------------------------------------------------------------------------------
 // grid: x = N tiles (fast index, so neighbouring blocks share the A row panel), y = M tiles.
-template <bool W4, bool FAST>
+template <bool W4, bool FAST = false>  // FAST: whole 16-byte loads (aligned operands whose K is a multiple of the chunk); unused since those shapes take the LDS-DMA path
 __global__ __launch_bounds__(kGemmThreads) void qgemm_k(const int8_t* __restrict__ A,
                                                         const void* __restrict__ Wv, int64_t M,
                                                         int64_t N, int64_t K,
                                                         const float* __restrict__ a_scale,
                                                         const float* __restrict__ w_scale,
                                                         int w_per_row, float* __restrict__ Y,
-                                                        int32_t* __restrict__ ACC) {
+                                                        int32_t* __restrict__ ACC,
+                                                        const float* __restrict__ YREF,
+                                                        double* __restrict__ PART) {
   __shared__ __attribute__((aligned(16))) int8_t lds_a[BM * BK];
   __shared__ __attribute__((aligned(16))) int8_t lds_b[BN * BK];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -168,12 +170,14 @@ __global__ __launch_bounds__(kGemmThreads) void qgemm_k(const int8_t* __restrict
   }
 
   // epilogue: lane holds column l%32 and rows 8*(v/4) + 4*(l/32) + v%4 of each 32x32 tile
-  const float sa = Y ? a_scale[0] : 0.0f;
+  const bool want_y = Y || YREF;
+  const float sa = want_y ? a_scale[0] : 0.0f;
+  float sse = 0.0f;  // this lane's share of sum (Y - YREF)^2
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
     const int64_t n = n0 + wn * 64 + j * 32 + (lane & 31);
     if (n >= N) continue;
-    const float sw = Y ? w_scale[w_per_row ? n : 0] : 0.0f;
+    const float sw = want_y ? w_scale[w_per_row ? n : 0] : 0.0f;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
 #pragma unroll
@@ -183,10 +187,39 @@ __global__ __launch_bounds__(kGemmThreads) void qgemm_k(const int8_t* __restrict
         int a = acc[i][j][v];
         if (W4) a >>= 4;  // exact: every product carried the factor 16
         if (ACC) ACC[m * N + n] = a;
-        if (Y) Y[m * N + n] = ((float)a * sa) * sw;
+        const float y = ((float)a * sa) * sw;
+        if (Y) Y[m * N + n] = y;
+        if (YREF) {
+          const float d = y - YREF[m * N + n];
+          sse = __builtin_fmaf(d, d, sse);
+        }
       }
     }
   }
+  if (PART) {  // one partial per workgroup, combined in a fixed order
+    const float w = wave_sum(sse);
+    __syncthreads();  // the tiles in LDS are not needed any more
+    float* sm = reinterpret_cast<float*>(lds_a);
+    if (lane == 0) sm[wave] = w;
+    __syncthreads();
+    if (threadIdx.x == 0)
+      PART[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = ((double)sm[0] + (double)sm[1]) + ((double)sm[2] + (double)sm[3]);
+  }
+}
+
+// sum of `count` per-workgroup partials, one workgroup, fixed order
+__global__ __launch_bounds__(kBlock) void sum_partials_k(const double* __restrict__ part, int64_t count,
+                                                         double* __restrict__ out) {
+  __shared__ double sm[kBlock];
+  double a = 0.0;
+  for (int64_t i = threadIdx.x; i < count; i += kBlock) a += part[i];
+  sm[threadIdx.x] = a;
+  __syncthreads();
+  for (int h = kBlock / 2; h > 0; h >>= 1) {
+    if ((int)threadIdx.x < h) sm[threadIdx.x] += sm[threadIdx.x + h];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) out[0] = sm[0];
 }
 
 
@@ -387,58 +420,75 @@ __device__ __forceinline__ unsigned xor_here(unsigned base) {
   return r;
 }
 
-// operand fragments of k-substep S (32 k-values) of the stage at byte offset stage_off
-template <class C, bool W4, int S>
-__device__ __forceinline__ void dma_load_frags(const char* lds, unsigned stage_off, const FragBase<C, W4>& fr,
-                                               v4i (&fa)[C::FM], v4i (&fb)[C::FN]) {
-  constexpr int DBK = C::DBK;
-  // logical chunk 2 S + g of an int8 row; packed rows hold 32 values per chunk: chunk S, half g
-  const char* pa = lds + xor_here<(unsigned)(S << 5)>(fr.a + stage_off);
-  const char* pb = lds + xor_here<(unsigned)(W4 ? S << 4 : S << 5)>(fr.b + stage_off);
-#pragma unroll
-  for (int i = 0; i < C::FM; ++i) fa[i] = *reinterpret_cast<const v4i*>(pa + i * 32 * DBK);
-#pragma unroll
-  for (int j = 0; j < C::FN; ++j) {
-    if (!W4) {
-      fb[j] = *reinterpret_cast<const v4i*>(pb + j * 32 * DBK);
-    } else {
-      const uint2 pk = *reinterpret_cast<const uint2*>(pb + j * 32 * (DBK / 2));
-      unsigned b0, b1, b2, b3;
-      expand8(pk.x, b0, b1);
-      expand8(pk.y, b2, b3);
-      fb[j] = v4i{(int)b0, (int)b1, (int)b2, (int)b3};
-    }
-  }
+// W fragment as it sits in LDS: the MFMA operand itself, or 16 packed nibbles that are expanded
+// right before use (kept packed meanwhile: half the registers, and the expansion then never waits
+// for a read issued a moment ago).
+template <bool W4>
+struct BRaw { v4i v; };
+template <>
+struct BRaw<true> { uint2 v; };
+__device__ __forceinline__ v4i b_operand(const BRaw<false>& r) { return r.v; }
+__device__ __forceinline__ v4i b_operand(const BRaw<true>& r) {
+  unsigned b0, b1, b2, b3;
+  expand8(r.v.x, b0, b1);
+  expand8(r.v.y, b2, b3);
+  return v4i{(int)b0, (int)b1, (int)b2, (int)b3};
 }
 
-template <class C>
-__device__ __forceinline__ void dma_mfma_substep(v16i (&acc)[C::FM][C::FN], const v4i (&fa)[C::FM],
-                                                 const v4i (&fb)[C::FN]) {
+// A fragments of k-substep S (32 k-values) of the stage at byte offset stage_off
+template <class C, bool W4, int S>
+__device__ __forceinline__ void load_a_frags(const char* lds, unsigned stage_off, const FragBase<C, W4>& fr,
+                                             v4i (&fa)[C::FM]) {
+  // logical chunk 2 S + g of an int8 row
+  const char* pa = lds + xor_here<(unsigned)(S << 5)>(fr.a + stage_off);
 #pragma unroll
-  for (int i = 0; i < C::FM; ++i)
-#pragma unroll
-    for (int j = 0; j < C::FN; ++j)
+  for (int i = 0; i < C::FM; ++i) fa[i] = *reinterpret_cast<const v4i*>(pa + i * 32 * C::DBK);
+}
+// LDS address of the lane's W fragments of k-substep S (packed rows hold 32 values per chunk:
+// chunk S, half g)
+template <class C, bool W4, int S>
+__device__ __forceinline__ const char* b_frag_ptr(const char* lds, unsigned stage_off, const FragBase<C, W4>& fr) {
+  return lds + xor_here<(unsigned)(W4 ? S << 4 : S << 5)>(fr.b + stage_off);
+}
+template <class C, bool W4>
+__device__ __forceinline__ void load_b_frag(const char* pb, int j, BRaw<W4>& fb) {
+  if constexpr (!W4) fb.v = *reinterpret_cast<const v4i*>(pb + j * 32 * C::DBK);
+  else fb.v = *reinterpret_cast<const uint2*>(pb + j * 32 * (C::DBK / 2));
+}
+
+// One k substep.  The operand reads of the FOLLOWING substep (S_NEXT of the stage at next_off) are
+// dealt in between the MFMAs: its A fragments first, into the other half of a double buffer; its
+// W fragment j into the registers of this substep's W fragment j as soon as the MFMAs that use
+// that one have been issued.  Every fragment is thus requested several MFMAs before its first
+// use, with 32 instead of 48 registers of fragments.  Left to itself the scheduler sinks every
+// read down to its first use, and a substep then starts by waiting out the LDS latency, hence
+// the pinning.
+// `request(r)` issues the wave's r-th global->LDS request of a k tile; NR of them are dealt out
+// over the substep (NR = 0: none).  A wave that issues its requests back to back sits in the
+// queue of the CU's one address unit (a 64 KiB k tile keeps it busy for about a thousand clocks)
+// and, issuing in order, feeds no MFMAs meanwhile.
+template <class C, bool W4, int S_NEXT, int NR, class Request>
+__device__ __forceinline__ void k_substep(v16i (&acc)[C::FM][C::FN], const v4i (&fa)[C::FM],
+                                          v4i (&fa_next)[C::FM], BRaw<W4> (&fb)[C::FN], const char* lds,
+                                          unsigned next_off, const FragBase<C, W4>& fr, Request&& request) {
+  constexpr int NM = C::FM * C::FN;
+  load_a_frags<C, W4, S_NEXT>(lds, next_off, fr, fa_next);
+  const char* pb = b_frag_ptr<C, W4, S_NEXT>(lds, next_off, fr);
+  __builtin_amdgcn_sched_barrier(0);
+  static_for<0, C::FN>([&](auto j_) {
+    constexpr int j = decltype(j_)::value;
+    const v4i b = b_operand(fb[j]);
+    static_for<0, C::FM>([&](auto i_) {
+      constexpr int i = decltype(i_)::value;
+      constexpr int q = j * C::FM + i;
+      static_for<q * NR / NM, (q + 1) * NR / NM>([&](auto r_) { request(r_); });
+      __builtin_amdgcn_sched_barrier(0);
       // W fragment as the row operand: the lane then holds 4 consecutive n per register group,
       // which the epilogue stores as one 16-byte piece of a Y row
-      acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[j], fa[i], acc[i][j], 0, 0, 0);
-}
-
-// The same MFMAs with the wave's requests for a k tile dealt out between them.  A wave that
-// issues its requests back to back sits in the queue of the CU's one address unit (64 bytes per
-// clock, so a 64 KiB k tile keeps it busy for about a thousand clocks) and, issuing in order,
-// feeds no MFMAs meanwhile; dealt out, the matrix pipe keeps working while the queue drains.
-template <class C, bool W4>
-__device__ __forceinline__ void dma_mfma_substep_requesting(v16i (&acc)[C::FM][C::FN], const v4i (&fa)[C::FM],
-                                                            const v4i (&fb)[C::FN], const DmaPlan<C, W4>& plan,
-                                                            const typename DmaPlan<C, W4>::Tile& tl,
-                                                            unsigned lds_stage_off) {
-  constexpr int NM = C::FM * C::FN, NR = C::LPW;
-  static_for<0, NM>([&](auto q_) {
-    constexpr int q = decltype(q_)::value;
-    static_for<q * NR / NM, (q + 1) * NR / NM>([&](auto r_) { plan.template request<decltype(r_)::value>(tl, lds_stage_off); });
-    __builtin_amdgcn_sched_barrier(0);
-    constexpr int i = q / C::FN, j = q % C::FN;
-    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[j], fa[i], acc[i][j], 0, 0, 0);
+      acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(b, fa[i], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    load_b_frag<C, W4>(pb, j, fb[j]);
     __builtin_amdgcn_sched_barrier(0);
   });
 }
@@ -455,14 +505,18 @@ __device__ __forceinline__ void dma_mfma_substep_requesting(v16i (&acc)[C::FM][C
 // that a tile always starts in stage 0.)  Chunks stay short so that the hardware dispatcher, not a
 // fixed assignment, balances the load when other kernels hold some of the CUs.
 // MINW: waves the register allocation must leave room for on one SIMD.
-template <int BM, int BN, int WM, int WN, int NSTAGE, bool W4, bool VEC, int KB, int MINW>
+// SCORE: also accumulate sum (Y - YREF)^2, one partial per workgroup (a variant of its own: the
+// largest tile has no registers to spare for it in the plain kernel).
+template <int BM, int BN, int WM, int WN, int NSTAGE, bool W4, bool VEC, int KB, int MINW, bool SCORE>
 __global__ __launch_bounds__(WM * WN * 64, MINW) void qgemm_dma(const int8_t* __restrict__ A,
                                                           const void* __restrict__ Wv, int64_t M,
                                                           int64_t N, int64_t K,
                                                           const float* __restrict__ a_scale,
                                                           const float* __restrict__ w_scale,
                                                           int w_per_row, float* __restrict__ Y,
-                                                          int32_t* __restrict__ ACC, int tiles_n,
+                                                          int32_t* __restrict__ ACC,
+                                                          const float* __restrict__ YREF,
+                                                          double* __restrict__ PART, int tiles_n,
                                                           int tiles_m, int chunk, int remap) {
   using C = DmaCfg<BM, BN, WM, WN, NSTAGE, W4, KB>;
   constexpr int DBK = KB;
@@ -490,7 +544,8 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void qgemm_dma(const int8_t* __
   // Per-channel W scales of an output tile travel through LDS (one wave-load of 256 floats, issued
   // by every wave ahead of the tile's first k tile, into the buffer `par` selects): the epilogue
   // then needs no global loads between its stores and no registers to park the scales in.
-  const bool lds_scales = VEC && Y && w_per_row;
+  const bool want_y = Y || (SCORE && YREF);
+  const bool lds_scales = VEC && want_y && w_per_row;
   unsigned par = 0;
   auto issue_scales = [&](int64_t n_first, unsigned which) {
     if (lds_scales) {  // wave-uniform
@@ -512,10 +567,17 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void qgemm_dma(const int8_t* __
   for (int p = 0; p < NSTAGE; ++p) plan.issue(lds0 + p * C::STAGE, p * DBK, k_limit);
   wait_vmcnt<(NSTAGE - 1) * C::LPW>();  // this wave's share of k tile 0 has landed
   __syncthreads();                      // ... and everyone else's
-  v4i fa[2][C::FM], fb[2][C::FN];
+  v4i fa[2][C::FM];
+  BRaw<W4> fb[C::FN];
   FragBase<C, W4> fr;
   fr.init(wm, wn, lane);
-  dma_load_frags<C, W4, 0>(lds, 0u, fr, fa[0], fb[0]);
+  load_a_frags<C, W4, 0>(lds, 0u, fr, fa[0]);
+  {
+    const char* pb = b_frag_ptr<C, W4, 0>(lds, 0u, fr);
+#pragma unroll
+    for (int j = 0; j < C::FN; ++j) load_b_frag<C, W4>(pb, j, fb[j]);
+  }
+  float sse = 0.0f;    // this lane's share of sum (Y - YREF)^2 over the chunk
   bool drain = false;  // true for the first wait after an epilogue: stores are in flight, and
                        // loads and stores do not retire in order with respect to each other
 
@@ -545,7 +607,8 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void qgemm_dma(const int8_t* __
         static_for<0, NSUB>([&](auto sub_) {
           constexpr int sub = decltype(sub_)::value;
           if constexpr (sub + 1 < NSUB) {
-            dma_load_frags<C, W4, sub + 1>(lds, (unsigned)(u * C::STAGE), fr, fa[(sub + 1) & 1], fb[(sub + 1) & 1]);
+            k_substep<C, W4, sub + 1, 0>(acc, fa[sub & 1], fa[(sub + 1) & 1], fb, lds, (unsigned)(u * C::STAGE), fr,
+                                         [](auto) {});
           } else {
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wave has read the stage for the last time
             if (drain) wait_vmcnt<0>();                          // its share of the next k tile has landed
@@ -554,18 +617,11 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void qgemm_dma(const int8_t* __
             __syncthreads();
             const int k_next = tail ? u * DBK : (kt + u + NSTAGE) * DBK;
             if (u == 0 && tail && next < tile_end) issue_scales(n0, par ^ 1u);
-            dma_load_frags<C, W4, 0>(lds, (unsigned)(((u + 1) % NSTAGE) * C::STAGE), fr, fa[0], fb[0]);
             const auto tl = plan.tile(k_next, k_limit);
-            __builtin_amdgcn_sched_barrier(0);
-            dma_mfma_substep_requesting<C, W4>(acc, fa[sub & 1], fb[sub & 1], plan, tl, lds0 + u * C::STAGE);
-          }
-          // Pin the order "operand reads of the next substep, then the MFMAs of this one": left to
-          // itself the scheduler sinks the reads down to their first use, and every substep then
-          // starts by waiting out the LDS latency.
-          if constexpr (sub + 1 < NSUB) {
-            __builtin_amdgcn_sched_barrier(0);
-            dma_mfma_substep<C>(acc, fa[sub & 1], fb[sub & 1]);
-            __builtin_amdgcn_sched_barrier(0);
+            // the stage just given up is refilled while the last substep's MFMAs, whose operands
+            // are in registers, run; the next stage's first fragments are read alongside
+            k_substep<C, W4, 0, C::LPW>(acc, fa[sub & 1], fa[0], fb, lds, (unsigned)(((u + 1) % NSTAGE) * C::STAGE), fr,
+                                        [&](auto r_) { plan.template request<decltype(r_)::value>(tl, lds0 + u * C::STAGE); });
           }
         });
       });
@@ -573,8 +629,8 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void qgemm_dma(const int8_t* __
 
     // epilogue.  32x32 accumulator tile (i, j): lane l holds m = l % 32 and, in registers
     // 4g .. 4g+3, the four consecutive n = 8g + 4 (l / 32) + 0..3.
-    const float sa = Y ? a_scale[0] : 0.0f;
-    const float sw0 = (Y && !w_per_row) ? w_scale[0] : 0.0f;
+    const float sa = want_y ? a_scale[0] : 0.0f;
+    const float sw0 = (want_y && !w_per_row) ? w_scale[0] : 0.0f;
     const char* scales = lds + C::SCALE_OFF + par * 1024u;
 #pragma unroll
     for (int i = 0; i < C::FM; ++i) {
@@ -594,20 +650,38 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void qgemm_dma(const int8_t* __
           }
           if (VEC) {  // N % 4 == 0 and 16-byte aligned outputs: the four n are all in range
             if (ACC) *reinterpret_cast<v4i*>(ACC + m * N + n) = v4i{a[0], a[1], a[2], a[3]};
-            if (Y) {
+            if (want_y) {
               float4 sw = make_float4(sw0, sw0, sw0, sw0);
               if (w_per_row)
                 sw = *reinterpret_cast<const float4*>(scales + (wn * C::TN + j * 32 + g4 * 8 + (lane >> 5) * 4) * 4);
-              *reinterpret_cast<float4*>(Y + m * N + n) =
-                  make_float4(((float)a[0] * sa) * sw.x, ((float)a[1] * sa) * sw.y,
-                              ((float)a[2] * sa) * sw.z, ((float)a[3] * sa) * sw.w);
+              const float4 y = make_float4(((float)a[0] * sa) * sw.x, ((float)a[1] * sa) * sw.y,
+                                           ((float)a[2] * sa) * sw.z, ((float)a[3] * sa) * sw.w);
+              if (Y) *reinterpret_cast<float4*>(Y + m * N + n) = y;
+              if (SCORE && YREF) {
+                const float4 r = *reinterpret_cast<const float4*>(YREF + m * N + n);
+                float d = y.x - r.x;
+                sse = __builtin_fmaf(d, d, sse);
+                d = y.y - r.y;
+                sse = __builtin_fmaf(d, d, sse);
+                d = y.z - r.z;
+                sse = __builtin_fmaf(d, d, sse);
+                d = y.w - r.w;
+                sse = __builtin_fmaf(d, d, sse);
+              }
             }
           } else {
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
               if (n + e >= N) break;
               if (ACC) ACC[m * N + n + e] = a[e];
-              if (Y) Y[m * N + n + e] = ((float)a[e] * sa) * (w_per_row ? w_scale[n + e] : sw0);
+              if (want_y) {
+                const float y = ((float)a[e] * sa) * (w_per_row ? w_scale[n + e] : sw0);
+                if (Y) Y[m * N + n + e] = y;
+                if (SCORE && YREF) {
+                  const float d = y - YREF[m * N + n + e];
+                  sse = __builtin_fmaf(d, d, sse);
+                }
+              }
             }
           }
         }
@@ -619,23 +693,41 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void qgemm_dma(const int8_t* __
     drain = true;
   }
   wait_vmcnt<0>();  // the zero-fill requests past the last tile land before the LDS is given back
+  if (SCORE && PART) {  // one partial per workgroup, combined in a fixed order
+    const float w = wave_sum(sse);
+    __syncthreads();  // nobody reads a stage or a scale buffer any more
+    float* sm = reinterpret_cast<float*>(lds);
+    if (lane == 0) sm[wave] = w;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      double t = 0.0;
+      for (int i = 0; i < C::NW; ++i) t += (double)sm[i];
+      PART[blockIdx.x] = t;
+    }
+  }
 }
 
 template <int BM, int BN, int WM, int WN, int NSTAGE, bool W4, int KB = 128, int MINW = 1>
 static int launch_dma(const int8_t* a_q, const void* w_q, int64_t M, int64_t N, int64_t K,
                       const float* a_scale, const float* w_scale, int per_row, float* y_out,
-                      int32_t* acc_out, hipStream_t st) {
+                      int32_t* acc_out, hipStream_t st, const float* y_ref = nullptr,
+                      double* partials = nullptr, int64_t* n_partials = nullptr) {
   using C = DmaCfg<BM, BN, WM, WN, NSTAGE, W4, KB>;
   // float4 / int4 stores need every 4-group of n inside the row and 16-byte aligned
   const bool vec = (N & 3) == 0 && (!y_out || aligned16(y_out)) && (!acc_out || aligned16(acc_out)) &&
-                   (!(y_out && per_row) || aligned16(w_scale));
-  auto kern = vec ? qgemm_dma<BM, BN, WM, WN, NSTAGE, W4, true, KB, MINW> : qgemm_dma<BM, BN, WM, WN, NSTAGE, W4, false, KB, MINW>;
-  static bool attr_set[2] = {false, false};  // dynamic LDS above 64 KiB has to be allowed once per kernel
-  if (!attr_set[vec]) {
+                   (!((y_out || y_ref) && per_row) || aligned16(w_scale)) && (!y_ref || aligned16(y_ref));
+  const bool score = y_ref != nullptr;
+  auto kern = score ? (vec ? qgemm_dma<BM, BN, WM, WN, NSTAGE, W4, true, KB, MINW, true>
+                           : qgemm_dma<BM, BN, WM, WN, NSTAGE, W4, false, KB, MINW, true>)
+                    : (vec ? qgemm_dma<BM, BN, WM, WN, NSTAGE, W4, true, KB, MINW, false>
+                           : qgemm_dma<BM, BN, WM, WN, NSTAGE, W4, false, KB, MINW, false>);
+  static bool attr_set[4] = {false, false, false, false};  // dynamic LDS above 64 KiB has to be allowed once per kernel
+  const int which = (score ? 2 : 0) + (vec ? 1 : 0);
+  if (!attr_set[which]) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
     if (e != hipSuccess) { set_last_hip_error((int)e); return MPQ_ERR_HIP; }
-    attr_set[vec] = true;
+    attr_set[which] = true;
   }
   const int64_t tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN;
   if (tm * tn > 0x7FFFFFFF || tn > 0x7FFFFFFF) return MPQ_ERR_SHAPE;
@@ -655,9 +747,64 @@ static int launch_dma(const int8_t* a_q, const void* w_q, int64_t M, int64_t N, 
   }
   const int remap = (grid % 8 == 0 && grid >= 16) ? 1 : 0;
   kern<<<(unsigned)grid, C::NT, C::LDS_BYTES, st>>>(a_q, w_q, M, N, K, a_scale, w_scale, per_row, y_out,
-                                                   acc_out, (int)tn, (int)tm, chunk, remap);
+                                                   acc_out, y_ref, partials, (int)tn, (int)tm, chunk, remap);
+  if (n_partials) *n_partials = grid;
   return launch_status();
 }
+
+// Validation and dispatch shared by mpq_qgemm and mpq_qgemm_score.  With y_ref the kernels also
+// leave one partial sum of (Y - y_ref)^2 per workgroup in `partials` and report how many.
+static int run_qgemm(const int8_t* a_q, const void* w_q, int w_storage_bits, int64_t M, int64_t N,
+                     int64_t K, const float* a_scale, const float* w_scale, int w_gran, float* y_out,
+                     int32_t* acc_out, const float* y_ref, double* partials, int64_t* n_partials,
+                     hipStream_t st) {
+  if (!a_q || !w_q) return MPQ_ERR_NULL;
+  if (!y_out && !acc_out && !y_ref) return MPQ_ERR_NULL;
+  if ((y_out || y_ref) && (!a_scale || !w_scale)) return MPQ_ERR_NULL;
+  if (w_storage_bits != 8 && w_storage_bits != 4) return MPQ_ERR_BITS;
+  if (M <= 0 || N <= 0 || K <= 0) return MPQ_ERR_SHAPE;
+  if (K > 133143) return MPQ_ERR_SHAPE;  // K * 127 * 127 must stay below 2^31
+  if (w_storage_bits == 4 && (K & 1)) return MPQ_ERR_SHAPE;
+  if (mul_overflows(M, N) || mul_overflows(M, K) || mul_overflows(N, K)) return MPQ_ERR_SHAPE;
+  if (w_gran != MPQ_PER_TENSOR && w_gran != MPQ_PER_ROW) return MPQ_ERR_GRAN;
+  if (y_out && (reinterpret_cast<uintptr_t>(y_out) & 3u)) return MPQ_ERR_ALIGN;
+  if (y_ref && (reinterpret_cast<uintptr_t>(y_ref) & 3u)) return MPQ_ERR_ALIGN;
+  if (acc_out && (reinterpret_cast<uintptr_t>(acc_out) & 3u)) return MPQ_ERR_ALIGN;
+  const int64_t gx = (N + BN - 1) / BN, gy = (M + BM - 1) / BM;
+  if (gx > 0x7FFFFFFF || gy > 65535) return MPQ_ERR_SHAPE;
+  const int per_row = w_gran == MPQ_PER_ROW;
+  const bool w4 = w_storage_bits == 4;
+  // the fast kernels index rows with 32 bits
+  const bool fast = aligned16(a_q) && aligned16(w_q) && (K % (w4 ? 32 : 16)) == 0 && M < (1ll << 31) && N < (1ll << 31);
+  if (fast) {
+    // tile choice (from sweeps over the configured shapes): 256 x 256 when that gives at least
+    // three CUs in four a tile, 128 x 128 when it gives at least half of them one, else 64 x 64.
+    // 128 x 128 runs three stages (one workgroup per CU) when there is at most one tile per CU
+    // anyway or k is long, two stages (two workgroups per CU) otherwise.
+    auto tiles = [&](int64_t bm, int64_t bn) { return ((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
+    int pick = 64;
+    if (N > 128 && tiles(256, 256) >= kNumCU * 3 / 4) pick = 256;
+    else if (N > 64 && tiles(128, 128) >= kNumCU / 2) pick = 128;
+#define MPQ_DMA(BM_, BN_, WM_, WN_, NS_)                                                              \
+  (w4 ? launch_dma<BM_, BN_, WM_, WN_, NS_, true>(a_q, w_q, M, N, K, a_scale, w_scale, per_row, y_out, \
+                                                  acc_out, st, y_ref, partials, n_partials)           \
+      : launch_dma<BM_, BN_, WM_, WN_, NS_, false>(a_q, w_q, M, N, K, a_scale, w_scale, per_row,     \
+                                                   y_out, acc_out, st, y_ref, partials, n_partials))
+    if (pick == 256) return MPQ_DMA(256, 256, 4, 2, 2);
+    if (pick == 128)
+      return (K >= 2048 || tiles(128, 128) <= kNumCU) ? MPQ_DMA(128, 128, 4, 2, 3) : MPQ_DMA(128, 128, 4, 2, 2);
+    return MPQ_DMA(64, 64, 2, 2, 3);
+#undef MPQ_DMA
+  }
+  const dim3 grid((unsigned)gx, (unsigned)gy);
+  if (w4) qgemm_k<true><<<grid, kGemmThreads, 0, st>>>(a_q, w_q, M, N, K, a_scale, w_scale, per_row, y_out, acc_out, y_ref, partials);
+  else qgemm_k<false><<<grid, kGemmThreads, 0, st>>>(a_q, w_q, M, N, K, a_scale, w_scale, per_row, y_out, acc_out, y_ref, partials);
+  if (n_partials) *n_partials = gx * gy;
+  return launch_status();
+}
+
+// partials never outnumber the 64 x 64 tiles (the smallest tile any kernel here uses)
+static int64_t max_partials(int64_t M, int64_t N) { return ((M + 63) / 64) * ((N + 63) / 64); }
 
 }  // namespace mpq
 
@@ -671,49 +818,32 @@ extern "C" int mpq_qgemm(const int8_t* a_q, const void* w_q, int w_storage_bits,
                          void* stream) {
   (void)ws;
   (void)ws_bytes;
-  if (!a_q || !w_q) return MPQ_ERR_NULL;
   if (!y_out && !acc_out) return MPQ_ERR_NULL;
-  if (y_out && (!a_scale || !w_scale)) return MPQ_ERR_NULL;
-  if (w_storage_bits != 8 && w_storage_bits != 4) return MPQ_ERR_BITS;
-  if (M <= 0 || N <= 0 || K <= 0) return MPQ_ERR_SHAPE;
-  if (K > 133143) return MPQ_ERR_SHAPE;  // K * 127 * 127 must stay below 2^31
-  if (w_storage_bits == 4 && (K & 1)) return MPQ_ERR_SHAPE;
-  if (mul_overflows(M, N) || mul_overflows(M, K) || mul_overflows(N, K)) return MPQ_ERR_SHAPE;
-  if (w_gran != MPQ_PER_TENSOR && w_gran != MPQ_PER_ROW) return MPQ_ERR_GRAN;
-  if (y_out && (reinterpret_cast<uintptr_t>(y_out) & 3u)) return MPQ_ERR_ALIGN;
-  if (acc_out && (reinterpret_cast<uintptr_t>(acc_out) & 3u)) return MPQ_ERR_ALIGN;
-  const int64_t gx = (N + BN - 1) / BN, gy = (M + BM - 1) / BM;
-  if (gx > 0x7FFFFFFF || gy > 65535) return MPQ_ERR_SHAPE;
+  return run_qgemm(a_q, w_q, w_storage_bits, M, N, K, a_scale, w_scale, w_gran, y_out, acc_out, nullptr,
+                   nullptr, nullptr, (hipStream_t)stream);
+}
+
+extern "C" size_t mpq_qgemm_score_workspace_bytes(int64_t M, int64_t N, int64_t K, int w_storage_bits) {
+  (void)w_storage_bits;
+  if (M <= 0 || N <= 0 || K <= 0 || mul_overflows(M, N)) return 0;
+  return (size_t)max_partials(M, N) * sizeof(double);
+}
+
+extern "C" int mpq_qgemm_score(const int8_t* a_q, const void* w_q, int w_storage_bits, int64_t M,
+                               int64_t N, int64_t K, const float* a_scale, const float* w_scale,
+                               int w_gran, const float* y_ref, double* sse_out, float* y_out, void* ws,
+                               size_t ws_bytes, void* stream) {
+  if (!y_ref || !sse_out) return MPQ_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(sse_out) & 7u) return MPQ_ERR_ALIGN;
+  if (M <= 0 || N <= 0 || mul_overflows(M, N)) return MPQ_ERR_SHAPE;
+  if (!ws || ws_bytes < (size_t)max_partials(M, N) * sizeof(double)) return MPQ_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(ws) & 7u) return MPQ_ERR_ALIGN;
   hipStream_t st = (hipStream_t)stream;
-  const dim3 grid((unsigned)gx, (unsigned)gy);
-  const int per_row = w_gran == MPQ_PER_ROW;
-  const bool w4 = w_storage_bits == 4;
-  // the fast kernels index rows with 32 bits
-  const bool fast = aligned16(a_q) && aligned16(w_q) && (K % (w4 ? 32 : 16)) == 0 && M < (1ll << 31) && N < (1ll << 31);
-#define MPQ_LAUNCH(W4_, FAST_) \
-  qgemm_k<W4_, FAST_><<<grid, kGemmThreads, 0, st>>>(a_q, w_q, M, N, K, a_scale, w_scale, per_row, y_out, acc_out)
-  if (fast) {
-    // tile choice (from sweeps over the configured shapes): 256 x 256 when that gives at least
-    // three CUs in four a tile, 128 x 128 when it gives at least half of them one, else 64 x 64.
-    // 128 x 128 runs three stages (one workgroup per CU) when there is at most one tile per CU
-    // anyway or k is long, two stages (two workgroups per CU) otherwise.
-    auto tiles = [&](int64_t bm, int64_t bn) { return ((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
-    int pick = 64;
-    if (N > 128 && tiles(256, 256) >= kNumCU * 3 / 4) pick = 256;
-    else if (N > 64 && tiles(128, 128) >= kNumCU / 2) pick = 128;
-#define MPQ_DMA(BM_, BN_, WM_, WN_, NS_)                                                              \
-  (w4 ? launch_dma<BM_, BN_, WM_, WN_, NS_, true>(a_q, w_q, M, N, K, a_scale, w_scale, per_row, y_out, \
-                                                  acc_out, st)                                        \
-      : launch_dma<BM_, BN_, WM_, WN_, NS_, false>(a_q, w_q, M, N, K, a_scale, w_scale, per_row,     \
-                                                   y_out, acc_out, st))
-    if (pick == 256) return MPQ_DMA(256, 256, 4, 2, 2);
-    if (pick == 128)
-      return (K >= 2048 || tiles(128, 128) <= kNumCU) ? MPQ_DMA(128, 128, 4, 2, 3) : MPQ_DMA(128, 128, 4, 2, 2);
-    return MPQ_DMA(64, 64, 2, 2, 3);
-#undef MPQ_DMA
-  }
-  if (w4) { if (fast) MPQ_LAUNCH(true, true); else MPQ_LAUNCH(true, false); }
-  else { if (fast) MPQ_LAUNCH(false, true); else MPQ_LAUNCH(false, false); }
-#undef MPQ_LAUNCH
+  double* partials = reinterpret_cast<double*>(ws);
+  int64_t count = 0;
+  const int rc = run_qgemm(a_q, w_q, w_storage_bits, M, N, K, a_scale, w_scale, w_gran, y_out, nullptr, y_ref,
+                           partials, &count, st);
+  if (rc != MPQ_OK) return rc;
+  sum_partials_k<<<1, kBlock, 0, st>>>(partials, count, sse_out);
   return launch_status();
 }

@@ -21,8 +21,12 @@ EXPORTS = [
     "mpq_calibrate_absmax",
     "mpq_scale_from_absmax", "mpq_fake_quant", "mpq_quant_error_workspace_bytes",
     "mpq_quant_error", "mpq_noise_inject", "mpq_qgemm_workspace_bytes", "mpq_qgemm",
-    "mpq_sse_pair_workspace_bytes", "mpq_sse_pair",
+    "mpq_sse_pair_workspace_bytes", "mpq_sse_pair", "mpq_qgemm_score_workspace_bytes", "mpq_qgemm_score",
+    "mpq_search_bisection", "mpq_search_greedy",
 ]
+
+EVAL_FN = C.CFUNCTYPE(C.c_double, C.POINTER(C.c_int), C.c_int, C.c_void_p)
+SEARCH_ENSURE_TARGET = 1
 
 _lib = None
 
@@ -64,6 +68,11 @@ def lib():
         L.mpq_sse_pair_workspace_bytes.restype = sz
         L.mpq_sse_pair_workspace_bytes.argtypes = [i64]
         L.mpq_sse_pair.argtypes = [vp, vp, i64, vp, vp, sz, vp]
+        L.mpq_qgemm_score_workspace_bytes.restype = sz
+        L.mpq_qgemm_score_workspace_bytes.argtypes = [i64, i64, i64, ci]
+        L.mpq_qgemm_score.argtypes = [vp, vp, ci, i64, i64, i64, vp, vp, ci, vp, vp, vp, vp, sz, vp]
+        for f in (L.mpq_search_bisection, L.mpq_search_greedy):
+            f.argtypes = [vp, ci, vp, ci, C.c_double, ci, EVAL_FN, vp, vp, vp]
         for name in EXPORTS:
             getattr(L, name)  # raises AttributeError if the library lacks a declared symbol
         _lib = L
@@ -232,3 +241,62 @@ def sse_pair(y, y_ref, out=None, ws: Workspace = None):
     wp, wn = (ws or _default_ws).get(sse_pair_workspace_bytes(n))
     _check(lib().mpq_sse_pair(_ptr(y), _ptr(y_ref), n, _ptr(out), wp, wn, _stream()), "mpq_sse_pair")
     return out
+
+
+def qgemm_score_workspace_bytes(M, N, K, w_storage_bits=8) -> int:
+    return int(lib().mpq_qgemm_score_workspace_bytes(M, N, K, w_storage_bits))
+
+
+def qgemm_score(a_q, w_q, a_scale, w_scale, y_ref, w_storage_bits=8, w_gran=PER_TENSOR, want_y=False,
+                y=None, out=None, ws: Workspace = None):
+    """One quantized layer scored against y_ref in its epilogue.  Returns (sse float64[1], Y | None)."""
+    torch = _torch()
+    a_q = _dev2d(a_q, torch.int8)
+    M, K = a_q.shape
+    N = w_q.shape[0]
+    if y_ref.dtype != torch.float32 or tuple(y_ref.shape) != (M, N) or not y_ref.is_contiguous():
+        raise ValueError("qgemm_score needs a contiguous fp32 y_ref of shape [M, N]")
+    if want_y and y is None:
+        y = torch.empty((M, N), dtype=torch.float32, device=a_q.device)
+    if out is None:
+        out = torch.empty(1, dtype=torch.float64, device=a_q.device)
+    wp, wn = (ws or _default_ws).get(qgemm_score_workspace_bytes(M, N, K, w_storage_bits))
+    _check(lib().mpq_qgemm_score(_ptr(a_q), _ptr(w_q), w_storage_bits, M, N, K, _ptr(a_scale), _ptr(w_scale),
+                                 w_gran, _ptr(y_ref), _ptr(out), _ptr(y), wp, wn, _stream()), "mpq_qgemm_score")
+    return out, y
+
+
+def _search(fn, name, order, bit_widths, target, evaluate, flags):
+    n, nb = len(order), len(bit_widths)
+    c_order = (C.c_int * n)(*[int(v) for v in order])
+    c_bits = (C.c_int * nb)(*[int(v) for v in bit_widths])
+    out = (C.c_int * max(n, 1))()
+    n_evals = C.c_int(0)
+    failure = []
+
+    def trampoline(bits, n_layers, _user):
+        if failure:                       # an earlier evaluation raised: let the search run out
+            return float("-inf")
+        try:
+            return float(evaluate([bits[i] for i in range(n_layers)]))
+        except BaseException as e:        # never unwind through the C frames
+            failure.append(e)
+            return float("-inf")
+
+    cb = EVAL_FN(trampoline)
+    _check(fn(c_order, n, c_bits, nb, float(target), int(flags), cb, None, out, C.byref(n_evals)), name)
+    if failure:
+        raise failure[0]
+    return [out[i] for i in range(n)], n_evals.value
+
+
+def search_bisection(order, bit_widths, target, evaluate, ensure_target=False):
+    """Alg. 1.  order: layer ids by ascending sensitivity; evaluate(bits per layer) -> accuracy.
+    Returns (bits per layer, number of evaluations)."""
+    return _search(lib().mpq_search_bisection, "mpq_search_bisection", order, bit_widths, target, evaluate,
+                   SEARCH_ENSURE_TARGET if ensure_target else 0)
+
+
+def search_greedy(order, bit_widths, target, evaluate):
+    """Alg. 2.  Same arguments and result as search_bisection."""
+    return _search(lib().mpq_search_greedy, "mpq_search_greedy", order, bit_widths, target, evaluate, 0)

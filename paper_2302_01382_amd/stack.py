@@ -1,0 +1,105 @@
+"""A stack of linear layers scored under a per-layer bit configuration: the "Evaluate f(x, lw)" of
+the paper's searches (Alg. 1, Alg. 2) built from libmpq calls only.
+
+The model is y = W_L relu(... relu(W_1 x)): every layer's input is calibrated (max calibration,
+Sec. 3.1), quantized to `act_bits` (Eq. 1) and multiplied with the layer's weight codes at the
+width the configuration assigns to it (mpq_qgemm); the last layer takes the score against the fp32
+output of the unquantized model in its epilogue (mpq_qgemm_score).  The accuracy handed to the
+searches is 1 - SSE / ||Y_ref||^2, a stand-in for the task accuracy the paper evaluates, which
+needs its datasets and trained weights.  torch supplies device memory, the ReLU between layers and
+the fp32 reference output, nothing else.
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Sequence, Tuple
+
+from . import mpq
+
+
+class QuantStack:
+    def __init__(self, x, weights: Sequence, bit_widths: Sequence[int], act_bits: int = 8,
+                 w_gran: int = mpq.PER_ROW):
+        """x: fp32 device tensor [M, K_1]; weights: fp32 device tensors [N_l, K_l] with K_{l+1} = N_l;
+        bit_widths: the widths (2..8) a layer may be given."""
+        import torch
+        self.torch = torch
+        self.x = x.contiguous()
+        self.weights = [w.contiguous() for w in weights]
+        self.bit_widths = [int(b) for b in bit_widths]
+        self.act_bits, self.w_gran = int(act_bits), w_gran
+        for a, b in zip(self.weights[:-1], self.weights[1:]):
+            if b.shape[1] != a.shape[0]:
+                raise ValueError("layer shapes do not chain")
+        if self.x.shape[1] != self.weights[0].shape[1]:
+            raise ValueError("input width does not match the first layer")
+        self.ws = mpq.Workspace()
+        dev, f32 = self.x.device, torch.float32
+        M = self.x.shape[0]
+        # fp32 reference output of the unquantized model
+        h = self.x
+        for i, w in enumerate(self.weights):
+            h = h @ w.t()
+            if i + 1 < len(self.weights):
+                h = torch.relu(h)
+        self.y_ref = h.contiguous()
+        self.ref_norm2 = float((self.y_ref.double() ** 2).sum().item())
+        # every weight at every width, once: codes (int8, or packed nibbles up to 4 bits) and steps
+        self.w_absmax = [mpq.calibrate_absmax(w, w_gran, ws=self.ws) for w in self.weights]
+        self.w_q: List[Dict[int, Tuple[object, object, int]]] = []
+        for w, am in zip(self.weights, self.w_absmax):
+            per_b = {}
+            for b in self.bit_widths:
+                store = 4 if (b <= 4 and w.shape[1] % 2 == 0) else 8
+                _, codes, packed = mpq.fake_quant(w, am, b, w_gran, want_y=False, want_codes=store == 8,
+                                                  want_packed4=store == 4)
+                per_b[b] = (codes if store == 8 else packed, mpq.scale_from_absmax(am, b), store)
+            self.w_q.append(per_b)
+        # buffers of one evaluation
+        self.a_absmax = [torch.empty(1, dtype=f32, device=dev) for _ in self.weights]
+        self.a_scale = [torch.empty(1, dtype=f32, device=dev) for _ in self.weights]
+        self.a_codes = [torch.empty((M, w.shape[1]), dtype=torch.int8, device=dev) for w in self.weights]
+        self.h = [torch.empty((M, w.shape[0]), dtype=f32, device=dev) for w in self.weights[:-1]]
+        self.sse = torch.empty(1, dtype=torch.float64, device=dev)
+        self.evaluations = 0
+
+    def __len__(self):
+        return len(self.weights)
+
+    def evaluate(self, bits: Sequence[int]) -> float:
+        """Accuracy 1 - SSE / ||Y_ref||^2 of the stack with layer l's weights at bits[l]."""
+        torch, P = self.torch, mpq
+        h = self.x
+        last = len(self.weights) - 1
+        for l in range(len(self.weights)):
+            P.calibrate_absmax(h, out=self.a_absmax[l], ws=self.ws)
+            P.fake_quant(h, self.a_absmax[l], self.act_bits, want_y=False, codes=self.a_codes[l])
+            P.scale_from_absmax(self.a_absmax[l], self.act_bits, out=self.a_scale[l])
+            wq, sw, store = self.w_q[l][int(bits[l])]
+            if l < last:
+                P.qgemm(self.a_codes[l], wq, self.a_scale[l], sw, store, self.w_gran, y=self.h[l], ws=self.ws)
+                h = torch.relu_(self.h[l])
+            else:
+                P.qgemm_score(self.a_codes[l], wq, self.a_scale[l], sw, self.y_ref, store, self.w_gran,
+                              out=self.sse, ws=self.ws)
+        self.evaluations += 1
+        return 1.0 - float(self.sse.item()) / self.ref_norm2   # the one read-back of an evaluation
+
+    def qe_sensitivity(self, b: int) -> List[float]:
+        """E_QE of Eq. 2 for every weight tensor at width b (per-tensor scale)."""
+        out = []
+        for w in self.weights:
+            am = mpq.calibrate_absmax(w, ws=self.ws)
+            sse = mpq.quant_error(w, am, b_lo=b, b_hi=b, ws=self.ws)
+            m = float(am.item())
+            out.append(0.0 if m == 0.0 else (float(sse.item()) / w.numel()) ** 0.5 / m)
+        return out
+
+    def order_by(self, sensitivity: Sequence[float]) -> List[int]:
+        """Layer ids in ascending order of sensitivity (ties: lower id first)."""
+        return sorted(range(len(self.weights)), key=lambda l: (sensitivity[l], l))
+
+    def bisection(self, order, target, ensure_target=True):
+        return mpq.search_bisection(order, sorted(self.bit_widths, reverse=True), target, self.evaluate, ensure_target)
+
+    def greedy(self, order, target):
+        return mpq.search_greedy(order, sorted(self.bit_widths, reverse=True), target, self.evaluate)

@@ -146,3 +146,24 @@ def cfg5_candidates(seed: int = 4, count: int = CFG5_CANDIDATES) -> List[Tuple[i
     bw = rng.choice([2, 4, 8], size=(count, 2))
     ba = rng.choice([4, 8], size=(count, 2))
     return [(int(bw[i, 0]), int(ba[i, 0]), int(bw[i, 1]), int(ba[i, 1])) for i in range(count)]
+
+
+# --- a stack of linear layers for the configuration searches (Alg. 1 / Alg. 2) ----------------
+def search_stack(seed: int = 6, layers: int = 8, width: int = 64, rows: int = 128):
+    """X [rows x width] ~ N(0,1) and `layers` square He-normal weights N(0, 2/width).  To give the
+    layers different sensitivities, 0.2 % of the entries of layer l are set to +-k_l sigma with a
+    seeded per-layer k_l in [3, 12]: the larger the outliers, the coarser the grid left for the
+    bulk of the weights at a given width."""
+    rng = _rng(seed, 6)
+    x = normal_f32(rng, (rows, width))
+    sigma = float(np.sqrt(2.0 / width))
+    k = 3.0 + 9.0 * rng.random(layers)
+    weights = []
+    for l in range(layers):
+        w = normal_f32(rng, (width, width), sigma)
+        n_out = max(1, int(round(0.002 * w.size)))
+        pos = rng.choice(w.size, size=n_out, replace=False)
+        sign = rng.integers(0, 2, size=n_out).astype(np.float32) * 2.0 - 1.0
+        w.reshape(-1)[pos] = np.float32(k[l] * sigma) * sign
+        weights.append(w)
+    return x, weights

@@ -156,6 +156,22 @@ def test_sse_pair_validation():
     assert f(FAKE16, FAKE16, 1 << 20, FAKE, FAKE16, need - 8, None) == mpq.ERR_WORKSPACE
 
 
+@needs_no_gpu
+def test_qgemm_score_validation():
+    L = mpq.lib()
+    f = L.mpq_qgemm_score
+    need = L.mpq_qgemm_score_workspace_bytes(256, 256, 64, 8)
+    assert need == 16 * 8 and L.mpq_qgemm_score_workspace_bytes(0, 4, 4, 8) == 0
+    head = (FAKE16, FAKE16, 8, 256, 256, 64, FAKE, FAKE, 0)
+    assert f(*head, None, FAKE16, None, FAKE16, need, None) == mpq.ERR_NULL          # no y_ref
+    assert f(*head, FAKE16, None, None, FAKE16, need, None) == mpq.ERR_NULL          # no sse_out
+    assert f(*head, FAKE16, C.c_void_p(0x10004), None, FAKE16, need, None) == mpq.ERR_ALIGN
+    assert f(*head, FAKE16, FAKE16, None, None, 0, None) == mpq.ERR_WORKSPACE
+    assert f(*head, FAKE16, FAKE16, None, FAKE16, need - 8, None) == mpq.ERR_WORKSPACE
+    assert f(FAKE16, FAKE16, 6, 256, 256, 64, FAKE, FAKE, 0, FAKE16, FAKE16, None, FAKE16, need, None) == mpq.ERR_BITS
+    assert f(FAKE16, FAKE16, 8, 256, 256, 64, None, FAKE, 0, FAKE16, FAKE16, None, FAKE16, need, None) == mpq.ERR_NULL
+
+
 def test_python_errors_carry_the_message():
     with pytest.raises(mpq.MpqError) as e:
         mpq._check(mpq.ERR_BITS, "mpq_fake_quant")

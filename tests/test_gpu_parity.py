@@ -286,6 +286,59 @@ def test_qgemm_extreme_operands_and_single_outputs():
     np.testing.assert_array_equal(host(acc4), acc4o)
 
 
+# ------------------------------------------------------------------------------ qgemm + score
+def score_case(M, N, K, wbits, gran, seed):
+    q = 127 if wbits == 8 else 7
+    a, w = rand_codes((M, K), 127, seed), rand_codes((N, K), q, seed + 1)
+    ws = w if wbits == 8 else oracle.pack4(w)
+    r = np.random.Generator(np.random.PCG64(seed + 2))
+    sa = np.array([0.02], np.float32)
+    sw = (r.random(N if gran == mpq.PER_ROW else 1).astype(np.float32) + 0.5) * np.float32(1e-3)
+    y_o, _ = oracle.qgemm(a, ws, sa, sw, wbits, gran)
+    # a reference output near the quantized one, as the fp32 layer output is in a search
+    y_ref = (y_o + np.float32(0.05) * np.abs(y_o).mean() * r.standard_normal(y_o.shape)).astype(np.float32)
+    return a, ws, sa, sw, y_o, y_ref, oracle.sse_pair(y_o, y_ref)
+
+
+@pytest.mark.parametrize("mnk", GEMM_SHAPES)
+@pytest.mark.parametrize("wbits", [8, 4])
+def test_qgemm_score_small_shapes(mnk, wbits):
+    M, N, K = mnk
+    if wbits == 4 and K % 2:
+        pytest.skip("packed int4 needs an even K")
+    for gran in (mpq.PER_TENSOR, mpq.PER_ROW):
+        a, ws, sa, sw, y_o, y_ref, want = score_case(M, N, K, wbits, gran, 40)
+        for mk in (dev, dev_misaligned):   # the misaligned copies take the byte-wise kernel
+            sse, y = mpq.qgemm_score(mk(a), mk(ws), dev(sa), dev(sw), mk(y_ref), wbits, gran, want_y=True)
+            assert host(sse)[0] == pytest.approx(want, rel=RTOL_SSE)
+            np.testing.assert_allclose(host(y), y_o, rtol=RTOL_Y, atol=0)
+            sse2, none = mpq.qgemm_score(mk(a), mk(ws), dev(sa), dev(sw), mk(y_ref), wbits, gran)
+            assert none is None
+            assert host(sse2)[0] == host(sse)[0]   # same kernel, same order: reproducible
+
+
+@pytest.mark.parametrize("mnk,wbits", [((2048, 2048, 384), 8), ((4100, 4092, 160), 4), ((2085, 2046, 112), 8),
+                                        ((300, 200, 1152), 4), ((1568, 512, 1024), 8), ((6272, 256, 512), 4)])
+def test_qgemm_score_every_tile_size(mnk, wbits):
+    """Shapes that select the 64, 128 and 256 tiles, with ragged edges, N not a multiple of 4 and
+    several tiles per workgroup; the whole product is small enough for the oracle."""
+    M, N, K = mnk
+    a, ws, sa, sw, y_o, y_ref, want = score_case(M, N, K, wbits, mpq.PER_ROW, 50)
+    da, dw, dsa, dsw, dref = dev(a), dev(ws), dev(sa), dev(sw), dev(y_ref)
+    sse, none = mpq.qgemm_score(da, dw, dsa, dsw, dref, wbits, mpq.PER_ROW)
+    assert none is None
+    assert host(sse)[0] == pytest.approx(want, rel=RTOL_SSE)
+    sse_y, y = mpq.qgemm_score(da, dw, dsa, dsw, dref, wbits, mpq.PER_ROW, want_y=True)
+    assert host(sse_y)[0] == pytest.approx(want, rel=RTOL_SSE)
+    np.testing.assert_allclose(host(y), y_o, rtol=RTOL_Y, atol=0)
+    # y_ref == the layer's own output: the score is exactly zero
+    zero, _ = mpq.qgemm_score(da, dw, dsa, dsw, y, wbits, mpq.PER_ROW)
+    assert host(zero)[0] == 0.0
+    # a y_ref that is only 4-byte aligned takes the scalar epilogue
+    sse_m, _ = mpq.qgemm_score(da, dw, dsa, dsw, dev_misaligned(y_ref), wbits, mpq.PER_ROW)
+    assert host(sse_m)[0] == pytest.approx(want, rel=RTOL_SSE)
+
+
 # ---------------------------------------------------------------------------------- sse pair
 @pytest.mark.parametrize("n", [1, 7, 4096, 100003, 1 << 20])
 def test_sse_pair(n):
