@@ -16,6 +16,7 @@ Other workloads (the parity-test configurations, measured with the same machiner
           and per output channel, noise at every b = 2..8
     cfg5  64 candidate bit configurations of a BERT-large FFN block at M = 16384, back to back,
           the output score taken in the second GEMM's epilogue (cfg5-unfused: qgemm + sse_pair)
+    search  Alg. 1 / Alg. 2 over a 24-layer stack, evaluations per second
 All inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 """
 from __future__ import annotations
@@ -462,12 +463,57 @@ def cpu_baseline(workloads, sample_rows):
     }
 
 
+def run_search(torch, mpq, workloads, args):
+    """The loop the hot path exists for: Alg. 2 (greedy) and Alg. 1 (bisection) over a 24-layer
+    stack of 1024 x 1024 layers at M = 4096, every evaluation a chain of libmpq launches ending in
+    one read-back of the score.  Reports evaluations per second, eager and with one HIP graph per
+    (layer, width)."""
+    from paper_2302_01382_amd.stack import QuantStack
+    layers, width, rows, bits, target = 24, 1024, 4096, [8, 4, 2], 0.95
+    x, weights = workloads.search_stack(seed=6, layers=layers, width=width, rows=rows)
+    dx, dws = torch.from_numpy(x).cuda(), [torch.from_numpy(w).cuda() for w in weights]
+    res = {}
+    for mode, graphs in (("eager", False), ("hip_graph_per_layer_and_width", True)):
+        st = QuantStack(dx, dws, bits, 8, use_graphs=graphs)
+        order = st.order_by(st.qe_sensitivity(2))
+        for b in bits:                       # warm-up: every (layer, width) pair once
+            st.evaluate([b] * layers)
+        torch.cuda.synchronize()
+        st.evaluations = 0
+        t0 = time.perf_counter()
+        cfg_g, ev_g = st.greedy(order, target)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        cfg_b, ev_b = st.bisection(order, target)
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        res[mode] = {"greedy": {"evaluations": ev_g, "seconds": t1 - t0, "evaluations_per_s": ev_g / (t1 - t0),
+                                "mean_weight_bits": sum(cfg_g) / layers, "accuracy": st.evaluate(cfg_g)},
+                     "bisection": {"evaluations": ev_b, "seconds": t2 - t1, "evaluations_per_s": ev_b / (t2 - t1),
+                                   "mean_weight_bits": sum(cfg_b) / layers, "accuracy": st.evaluate(cfg_b)}}
+    best = res["hip_graph_per_layer_and_width"]["greedy"]
+    ops_per_eval = 2.0 * rows * width * width * layers
+    out = {
+        "metric": "configuration-search evaluations/s (Alg. 2 greedy; each evaluation = the whole quantized stack)",
+        "value": best["evaluations_per_s"], "unit": "evaluations/s", "n_gpus": 1, "steps": best["evaluations"],
+        "warmup": len(bits), "ms_per_step": 1e3 / best["evaluations_per_s"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32 elementwise, int8 x int8 -> int32 GEMM",
+        "data": "synthetic",
+        "config": {"workload": "search: %d layers of %d x %d at M = %d, weight widths %s, activations 8 bit, "
+                               "target accuracy %.2f (1 - SSE/||Y_ref||^2), order by E_QE at b = 2"
+                               % (layers, width, width, rows, bits, target)},
+        "qgemm_tops_inside_an_evaluation": ops_per_eval * best["evaluations_per_s"] / 1e12,
+        "search": res,
+    }
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", choices=["cfg2", "cfg3", "cfg4", "cfg5", "cfg5-unfused"], default="cfg2")
+    ap.add_argument("--workload", choices=["cfg2", "cfg3", "cfg4", "cfg5", "cfg5-unfused", "search"], default="cfg2")
     ap.add_argument("--cpu-sample-rows", type=int, default=1024)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -488,6 +534,9 @@ def main():
     torch.cuda.set_device(0)
     mpq.lib()
 
+    if args.workload == "search":
+        run_search(torch, mpq, workloads, args)
+        return
     extra = {}
     traffic = None
     layers = None

@@ -18,9 +18,12 @@ from . import mpq
 
 class QuantStack:
     def __init__(self, x, weights: Sequence, bit_widths: Sequence[int], act_bits: int = 8,
-                 w_gran: int = mpq.PER_ROW):
+                 w_gran: int = mpq.PER_ROW, use_graphs: bool = False):
         """x: fp32 device tensor [M, K_1]; weights: fp32 device tensors [N_l, K_l] with K_{l+1} = N_l;
-        bit_widths: the widths (2..8) a layer may be given."""
+        bit_widths: the widths (2..8) a layer may be given.
+        use_graphs: the launches of layer l at width b (calibrate, quantize, step size, GEMM, ReLU)
+        are captured into a HIP graph the first time that pair is evaluated and replayed from then
+        on, so an evaluation costs one launch per layer instead of six."""
         import torch
         self.torch = torch
         self.x = x.contiguous()
@@ -61,28 +64,47 @@ class QuantStack:
         self.h = [torch.empty((M, w.shape[0]), dtype=f32, device=dev) for w in self.weights[:-1]]
         self.sse = torch.empty(1, dtype=torch.float64, device=dev)
         self.evaluations = 0
+        self.use_graphs = use_graphs
+        self.graphs = {}
 
     def __len__(self):
         return len(self.weights)
 
     def evaluate(self, bits: Sequence[int]) -> float:
         """Accuracy 1 - SSE / ||Y_ref||^2 of the stack with layer l's weights at bits[l]."""
-        torch, P = self.torch, mpq
-        h = self.x
-        last = len(self.weights) - 1
         for l in range(len(self.weights)):
-            P.calibrate_absmax(h, out=self.a_absmax[l], ws=self.ws)
-            P.fake_quant(h, self.a_absmax[l], self.act_bits, want_y=False, codes=self.a_codes[l])
-            P.scale_from_absmax(self.a_absmax[l], self.act_bits, out=self.a_scale[l])
-            wq, sw, store = self.w_q[l][int(bits[l])]
-            if l < last:
-                P.qgemm(self.a_codes[l], wq, self.a_scale[l], sw, store, self.w_gran, y=self.h[l], ws=self.ws)
-                h = torch.relu_(self.h[l])
-            else:
-                P.qgemm_score(self.a_codes[l], wq, self.a_scale[l], sw, self.y_ref, store, self.w_gran,
-                              out=self.sse, ws=self.ws)
+            b = int(bits[l])
+            if not self.use_graphs:
+                self._layer(l, b)
+                continue
+            g = self.graphs.get((l, b))
+            if g is None:
+                # once eagerly (sizes the workspace, so that nothing is allocated under capture),
+                # then captured; both leave the layer's output in place like a replay does
+                self._layer(l, b)
+                self.torch.cuda.synchronize()
+                g = self.torch.cuda.CUDAGraph()
+                with self.torch.cuda.graph(g):
+                    self._layer(l, b)
+                self.graphs[(l, b)] = g
+            g.replay()
         self.evaluations += 1
         return 1.0 - float(self.sse.item()) / self.ref_norm2   # the one read-back of an evaluation
+
+    def _layer(self, l: int, b: int):
+        """Layer l at weight width b: input h_{l-1} (x for the first layer) -> h_l, or the score."""
+        torch, P = self.torch, mpq
+        h = self.x if l == 0 else self.h[l - 1]
+        P.calibrate_absmax(h, out=self.a_absmax[l], ws=self.ws)
+        P.fake_quant(h, self.a_absmax[l], self.act_bits, want_y=False, codes=self.a_codes[l])
+        P.scale_from_absmax(self.a_absmax[l], self.act_bits, out=self.a_scale[l])
+        wq, sw, store = self.w_q[l][b]
+        if l + 1 < len(self.weights):
+            P.qgemm(self.a_codes[l], wq, self.a_scale[l], sw, store, self.w_gran, y=self.h[l], ws=self.ws)
+            torch.relu_(self.h[l])
+        else:
+            P.qgemm_score(self.a_codes[l], wq, self.a_scale[l], sw, self.y_ref, store, self.w_gran,
+                          out=self.sse, ws=self.ws)
 
     def qe_sensitivity(self, b: int) -> List[float]:
         """E_QE of Eq. 2 for every weight tensor at width b (per-tensor scale)."""

@@ -124,3 +124,18 @@ def test_search_result_matches_the_oracle_search(stacks, algorithm, target):
     assert evals_g == evals_o
     if any(b < 8 for b in got):
         assert gpu.evaluate(got) >= target - 2e-3 * (1.0 - target)
+
+
+def test_graph_replayed_evaluations_equal_eager_ones(stacks):
+    """Every (layer, width) pair captured into a HIP graph and replayed several times, with eager
+    evaluations in between: identical scores."""
+    gpu, orc, weights = stacks
+    x, _ = workloads.search_stack(width=96, rows=160, layers=10)
+    graphed = QuantStack(dev(x), [dev(w) for w in weights], BITS, ACT_BITS, use_graphs=True)
+    r = np.random.Generator(np.random.PCG64(9))
+    for _ in range(20):
+        bits = [int(v) for v in r.choice(BITS, len(weights))]
+        assert graphed.evaluate(bits) == gpu.evaluate(bits)
+    assert len(graphed.graphs) == len(weights) * len(BITS)
+    order = list(range(len(weights)))
+    assert graphed.greedy(order, 0.9) == gpu.greedy(order, 0.9)
