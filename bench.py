@@ -13,7 +13,8 @@ conv-as-GEMM stack (8 layers at batch 32).  Per layer a step runs, through the C
 Other workloads (the parity-test configurations, measured with the same machinery):
     cfg3  BERT-base encoder linears at M = 12288, same per-layer path, per-tensor scales
     cfg4  sensitivity sweep over the 96 BERT-large weight tensors: absmax + quant_error per tensor
-          and per output channel, noise at every b = 2..8
+          and per output channel, noise at every b = 2..8 from one call per tensor
+          (cfg4-unfused: one call per granularity and per noise level)
     cfg5  64 candidate bit configurations of a BERT-large FFN block at M = 16384, back to back,
           the output score taken in the second GEMM's epilogue (cfg5-unfused: qgemm + sse_pair)
     search  Alg. 1 / Alg. 2 over a 24-layer stack, evaluations per second
@@ -310,7 +311,7 @@ def workload_layers(torch, P, workloads, which):
 
 # ------------------------------------------------------------------------------------------------
 # configuration 4: sensitivity sweep over the BERT-large weight set
-def workload_cfg4(torch, P, workloads):
+def workload_cfg4(torch, P, workloads, fused):
     tensors = [torch.from_numpy(w).cuda() for _, w in workloads.cfg4_tensors()]
     dev = tensors[0].device
     f32, f64 = torch.float32, torch.float64
@@ -318,30 +319,43 @@ def workload_cfg4(torch, P, workloads):
     am_r = [torch.empty(t.shape[0], dtype=f32, device=dev) for t in tensors]
     sse_t = [torch.empty((1, 7), dtype=f64, device=dev) for _ in tensors]
     sse_r = [torch.empty((t.shape[0], 7), dtype=f64, device=dev) for t in tensors]
-    noisy = {tuple(t.shape): torch.empty_like(t) for t in tensors}  # one output buffer per shape
+    # one output buffer per shape: a plane per bit-width when the seven noise levels come from one call
+    noisy = {tuple(t.shape): torch.empty((7 if fused else 1,) + tuple(t.shape), dtype=f32, device=dev)
+             for t in tensors}
     ws = P.Workspace()
     ws.get(1 << 22)
 
     def step(rec):
         for i, t in enumerate(tensors):
             n = t.numel()
-            with rec("absmax", 8 * n):
-                P.calibrate_absmax(t, P.PER_TENSOR, out=am_t[i], ws=ws)
-                P.calibrate_absmax(t, P.PER_ROW, out=am_r[i])
+            if fused:   # the tensor's maximum is the maximum of its row maxima: one read of the tensor
+                with rec("absmax", 4 * n):
+                    P.calibrate_absmax(t, P.PER_ROW, out=am_r[i])
+                    P.calibrate_absmax(am_r[i].view(1, -1), P.PER_TENSOR, out=am_t[i], ws=ws)
+            else:
+                with rec("absmax", 8 * n):
+                    P.calibrate_absmax(t, P.PER_TENSOR, out=am_t[i], ws=ws)
+                    P.calibrate_absmax(t, P.PER_ROW, out=am_r[i])
             with rec("quant_error", 8 * n):
                 P.quant_error(t, am_t[i], 2, 8, P.PER_TENSOR, out=sse_t[i], ws=ws)
                 P.quant_error(t, am_r[i], 2, 8, P.PER_ROW, out=sse_r[i], ws=ws)
-            with rec("noise_inject", 7 * 8 * n):
-                for b in range(2, 9):
-                    P.noise_inject(t, am_r[i], b, LAMBDA, 2302, i, P.PER_ROW, out=noisy[tuple(t.shape)])
+            if fused:   # z does not depend on b: drawn once, seven outputs
+                with rec("noise_inject", (4 + 7 * 4) * n):
+                    P.noise_inject_sweep(t, am_r[i], 2, 8, LAMBDA, 2302, i, P.PER_ROW, out=noisy[tuple(t.shape)])
+            else:
+                with rec("noise_inject", 7 * 8 * n):
+                    for b in range(2, 9):
+                        P.noise_inject(t, am_r[i], b, LAMBDA, 2302, i, P.PER_ROW, out=noisy[tuple(t.shape)][0])
 
     def snapshot():
         return [s.clone() for s in sse_t] + [s.clone() for s in sse_r[:8]]
 
     n_total = sum(t.numel() for t in tensors)
     label = ("cfg4: sensitivity sweep over 96 BERT-large weight tensors (302 M elements): absmax + quant_error "
-             "b=2..8 per tensor and per output channel, noise at every b")
-    return step, snapshot, n_total * (8 + 8 + 56), 0, label
+             "b=2..8 per tensor and per output channel, noise at every b"
+             + (" (row maxima reused for the tensor maximum; the seven noise levels from one call)" if fused
+                else " (one call per granularity and per noise level)"))
+    return step, snapshot, n_total * ((4 + 8 + 32) if fused else (8 + 8 + 56)), 0, label
 
 
 # ------------------------------------------------------------------------------------------------
@@ -513,7 +527,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", choices=["cfg2", "cfg3", "cfg4", "cfg5", "cfg5-unfused", "search"], default="cfg2")
+    ap.add_argument("--workload", choices=["cfg2", "cfg3", "cfg4", "cfg4-unfused", "cfg5", "cfg5-unfused", "search"], default="cfg2")
     ap.add_argument("--cpu-sample-rows", type=int, default=1024)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -543,8 +557,8 @@ def main():
     if args.workload in ("cfg2", "cfg3"):
         step, snapshot, nbytes, ops, label, layers = workload_layers(torch, mpq, workloads, args.workload)
         traffic = TRAFFIC_KIB_PER_LAUNCH_CFG2 if args.workload == "cfg2" else None
-    elif args.workload == "cfg4":
-        step, snapshot, nbytes, ops, label = workload_cfg4(torch, mpq, workloads)
+    elif args.workload in ("cfg4", "cfg4-unfused"):
+        step, snapshot, nbytes, ops, label = workload_cfg4(torch, mpq, workloads, args.workload == "cfg4")
     else:
         step, snapshot, nbytes, ops, label, ncand = workload_cfg5(torch, mpq, workloads, args.workload == "cfg5")
         extra["candidates_per_step"] = ncand

@@ -110,6 +110,14 @@ int mpq_noise_inject(const float* x, int64_t rows, int64_t cols, int gran, const
                      int bits, float lambda, uint64_t seed, uint64_t stream_id, float* y_out,
                      void* stream);
 
+/* The same perturbation for every bit-width b_lo..b_hi in one pass (z does not depend on b and is
+ * drawn once per element): plane k of y_out, starting y_stride elements after plane k-1
+ * (y_stride >= rows*cols, else MPQ_ERR_SHAPE), holds exactly what mpq_noise_inject writes for
+ * bits = b_lo + k.  x must not overlap y_out. */
+int mpq_noise_inject_sweep(const float* x, int64_t rows, int64_t cols, int gran, const float* absmax,
+                           int b_lo, int b_hi, float lambda, uint64_t seed, uint64_t stream_id,
+                           float* y_out, int64_t y_stride, void* stream);
+
 /* ---- "Evaluate f(x, w)" of Alg. 1 / Alg. 2: one quantized linear layer ------------------------
  * acc[m][n] = sum_k a_q[m][k] * w_q[n][k] (int32), y[m][n] = fl32(fl32(float(acc) * a_scale[0])
  *             * w_scale[n or 0]).

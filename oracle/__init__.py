@@ -167,6 +167,12 @@ def noise_inject(x, absmax_arr, bits, lam, seed, stream_id, gran=PER_TENSOR):
     return y
 
 
+def noise_inject_sweep(x, absmax_arr, b_lo, b_hi, lam, seed, stream_id, gran=PER_TENSOR):
+    """Eq. 3-5 at every bit-width b_lo..b_hi: by definition one noise_inject per b (the draw z does not
+    depend on b, so all planes share it).  Returns [nb, rows, cols]."""
+    return np.stack([noise_inject(x, absmax_arr, b, lam, seed, stream_id, gran) for b in range(b_lo, b_hi + 1)])
+
+
 def pack4(codes):
     codes = np.ascontiguousarray(codes, dtype=np.int8)
     assert codes.size % 2 == 0

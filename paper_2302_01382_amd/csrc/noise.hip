@@ -112,26 +112,33 @@ __device__ __forceinline__ float sigma_of(float absmax, int bits, float lambda) 
 
 // ---- one sigma for the whole group of four: per tensor, or per row with cols % 4 == 0 -------
 // ROWS = false: flat; ROWS = true: group g lies in row g / (cols/4)
+// Both kernels write nb outputs, one per bit-width b_lo .. b_lo + nb - 1, `stride` elements apart:
+// z does not depend on b, so a sweep over bit-widths draws it once per element.
 template <bool ROWS>
 __global__ __launch_bounds__(kBlock) void noise_vec(const float* __restrict__ x, int64_t n4,
                                                     int64_t cols4, const float* __restrict__ absmax,
-                                                    int bits, float lambda, unsigned long long seed,
-                                                    unsigned long long sid, float* __restrict__ y) {
-  const float sig0 = ROWS ? 0.0f : sigma_of(absmax[0], bits, lambda);
+                                                    int b_lo, int nb, float lambda, unsigned long long seed,
+                                                    unsigned long long sid, float* __restrict__ y,
+                                                    int64_t stride4) {
   for_each_vec4_tiled(reinterpret_cast<const float4*>(x), n4, [&](const float4 v, int64_t g) {
-    const float sig = ROWS ? sigma_of(absmax[g / cols4], bits, lambda) : sig0;
+    const float m = absmax[ROWS ? g / cols4 : 0];
     const float4 z = gauss4(seed, sid, (unsigned long long)g);
-    reinterpret_cast<float4*>(y)[g] = make_float4(__builtin_fmaf(sig, z.x, v.x), __builtin_fmaf(sig, z.y, v.y),
-                                                  __builtin_fmaf(sig, z.z, v.z), __builtin_fmaf(sig, z.w, v.w));
+    for (int k = 0; k < nb; ++k) {
+      const float sig = sigma_of(m, b_lo + k, lambda);
+      reinterpret_cast<float4*>(y)[g + k * stride4] =
+          make_float4(__builtin_fmaf(sig, z.x, v.x), __builtin_fmaf(sig, z.y, v.y),
+                      __builtin_fmaf(sig, z.z, v.z), __builtin_fmaf(sig, z.w, v.w));
+    }
   });
 }
 
 // ---- generic: any shape, alignment, granularity; a lane still owns one group of four ----------
 __global__ __launch_bounds__(kBlock) void noise_generic(const float* __restrict__ x, int64_t rows,
                                                         int64_t cols, int gran,
-                                                        const float* __restrict__ absmax, int bits,
+                                                        const float* __restrict__ absmax, int b_lo, int nb,
                                                         float lambda, unsigned long long seed,
-                                                        unsigned long long sid, float* __restrict__ y) {
+                                                        unsigned long long sid, float* __restrict__ y,
+                                                        int64_t stride) {
   const int64_t n = rows * cols;
   const int64_t n4 = (n + 3) >> 2;
   for (int64_t g = (int64_t)blockIdx.x * kBlock + threadIdx.x; g < n4; g += (int64_t)gridDim.x * kBlock) {
@@ -143,10 +150,26 @@ __global__ __launch_bounds__(kBlock) void noise_generic(const float* __restrict_
       if (i < n) {
         const int64_t r = i / cols, c = i - r * cols;
         const int64_t ch = gran == MPQ_PER_ROW ? r : gran == MPQ_PER_COL ? c : 0;
-        y[i] = __builtin_fmaf(sigma_of(absmax[ch], bits, lambda), zz[e], x[i]);
+        const float m = absmax[ch], xi = x[i];
+        for (int k = 0; k < nb; ++k) y[i + k * stride] = __builtin_fmaf(sigma_of(m, b_lo + k, lambda), zz[e], xi);
       }
     }
   }
+}
+
+static int launch_noise(const float* x, int64_t rows, int64_t cols, int gran, const float* absmax, int b_lo,
+                        int nb, float lambda, uint64_t seed, uint64_t stream_id, float* y_out, int64_t stride,
+                        hipStream_t st) {
+  const int64_t n = rows * cols;
+  const bool vec = aligned16(x) && aligned16(y_out) && (n & 3) == 0 && (stride & 3) == 0;
+  if (vec && gran == MPQ_PER_TENSOR) {
+    noise_vec<false><<<flat_grid(n >> 2, kBlock * kTileVec), kBlock, 0, st>>>(x, n >> 2, 0, absmax, b_lo, nb, lambda, seed, stream_id, y_out, stride >> 2);
+  } else if (vec && gran == MPQ_PER_ROW && (cols & 3) == 0) {
+    noise_vec<true><<<flat_grid(n >> 2, kBlock * kTileVec), kBlock, 0, st>>>(x, n >> 2, cols >> 2, absmax, b_lo, nb, lambda, seed, stream_id, y_out, stride >> 2);
+  } else {
+    noise_generic<<<flat_grid((n + 3) >> 2, kBlock * 2), kBlock, 0, st>>>(x, rows, cols, gran, absmax, b_lo, nb, lambda, seed, stream_id, y_out, stride);
+  }
+  return launch_status();
 }
 
 }  // namespace mpq
@@ -160,15 +183,17 @@ extern "C" int mpq_noise_inject(const float* x, int64_t rows, int64_t cols, int 
   if (rows <= 0 || cols <= 0 || mul_overflows(rows, cols)) return MPQ_ERR_SHAPE;
   if (gran < MPQ_PER_TENSOR || gran > MPQ_PER_COL) return MPQ_ERR_GRAN;
   if (bits < 2 || bits > 8) return MPQ_ERR_BITS;
-  hipStream_t st = (hipStream_t)stream;
-  const int64_t n = rows * cols;
-  const bool vec = aligned16(x) && aligned16(y_out) && (n & 3) == 0;
-  if (vec && gran == MPQ_PER_TENSOR) {
-    noise_vec<false><<<flat_grid(n >> 2, kBlock * kTileVec), kBlock, 0, st>>>(x, n >> 2, 0, absmax, bits, lambda, seed, stream_id, y_out);
-  } else if (vec && gran == MPQ_PER_ROW && (cols & 3) == 0) {
-    noise_vec<true><<<flat_grid(n >> 2, kBlock * kTileVec), kBlock, 0, st>>>(x, n >> 2, cols >> 2, absmax, bits, lambda, seed, stream_id, y_out);
-  } else {
-    noise_generic<<<flat_grid((n + 3) >> 2, kBlock * 2), kBlock, 0, st>>>(x, rows, cols, gran, absmax, bits, lambda, seed, stream_id, y_out);
-  }
-  return launch_status();
+  return launch_noise(x, rows, cols, gran, absmax, bits, 1, lambda, seed, stream_id, y_out, 0, (hipStream_t)stream);
+}
+
+extern "C" int mpq_noise_inject_sweep(const float* x, int64_t rows, int64_t cols, int gran,
+                                      const float* absmax, int b_lo, int b_hi, float lambda, uint64_t seed,
+                                      uint64_t stream_id, float* y_out, int64_t y_stride, void* stream) {
+  if (!x || !absmax || !y_out) return MPQ_ERR_NULL;
+  if (rows <= 0 || cols <= 0 || mul_overflows(rows, cols)) return MPQ_ERR_SHAPE;
+  if (gran < MPQ_PER_TENSOR || gran > MPQ_PER_COL) return MPQ_ERR_GRAN;
+  if (b_lo < 2 || b_hi > 8 || b_lo > b_hi) return MPQ_ERR_BITS;
+  if (y_stride < rows * cols || mul_overflows(y_stride, 8)) return MPQ_ERR_SHAPE;  // planes must not overlap
+  return launch_noise(x, rows, cols, gran, absmax, b_lo, b_hi - b_lo + 1, lambda, seed, stream_id, y_out, y_stride,
+                      (hipStream_t)stream);
 }

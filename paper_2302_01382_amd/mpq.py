@@ -22,7 +22,7 @@ EXPORTS = [
     "mpq_scale_from_absmax", "mpq_fake_quant", "mpq_quant_error_workspace_bytes",
     "mpq_quant_error", "mpq_noise_inject", "mpq_qgemm_workspace_bytes", "mpq_qgemm",
     "mpq_sse_pair_workspace_bytes", "mpq_sse_pair", "mpq_qgemm_score_workspace_bytes", "mpq_qgemm_score",
-    "mpq_search_bisection", "mpq_search_greedy",
+    "mpq_search_bisection", "mpq_search_greedy", "mpq_noise_inject_sweep",
 ]
 
 EVAL_FN = C.CFUNCTYPE(C.c_double, C.POINTER(C.c_int), C.c_int, C.c_void_p)
@@ -62,6 +62,7 @@ def lib():
         L.mpq_quant_error_workspace_bytes.argtypes = [i64, i64, ci, ci, ci]
         L.mpq_quant_error.argtypes = [vp, i64, i64, ci, vp, ci, ci, vp, vp, sz, vp]
         L.mpq_noise_inject.argtypes = [vp, i64, i64, ci, vp, ci, C.c_float, C.c_uint64, C.c_uint64, vp, vp]
+        L.mpq_noise_inject_sweep.argtypes = [vp, i64, i64, ci, vp, ci, ci, C.c_float, C.c_uint64, C.c_uint64, vp, i64, vp]
         L.mpq_qgemm_workspace_bytes.restype = sz
         L.mpq_qgemm_workspace_bytes.argtypes = [i64, i64, i64, ci]
         L.mpq_qgemm.argtypes = [vp, vp, ci, i64, i64, i64, vp, vp, ci, vp, vp, vp, sz, vp]
@@ -201,6 +202,21 @@ def noise_inject(x, absmax, bits, lam, seed, stream_id, gran=PER_TENSOR, out=Non
         out = torch.empty_like(x)
     _check(lib().mpq_noise_inject(_ptr(x), rows, cols, gran, _ptr(absmax), bits, float(lam),
                                   int(seed), int(stream_id), _ptr(out), _stream()), "mpq_noise_inject")
+    return out
+
+
+def noise_inject_sweep(x, absmax, b_lo, b_hi, lam, seed, stream_id, gran=PER_TENSOR, out=None):
+    """Noise at every bit-width b_lo..b_hi in one pass; returns fp32 [nb, rows, cols]."""
+    torch = _torch()
+    x = _dev2d(x, torch.float32)
+    rows, cols = x.shape
+    nb = b_hi - b_lo + 1
+    if out is None:
+        out = torch.empty((max(nb, 1), rows, cols), dtype=torch.float32, device=x.device)
+    if out.dim() != 3 or tuple(out.shape[1:]) != (rows, cols) or not out[0].is_contiguous():
+        raise ValueError("noise_inject_sweep needs an output of shape [nb, rows, cols] with contiguous planes")
+    _check(lib().mpq_noise_inject_sweep(_ptr(x), rows, cols, gran, _ptr(absmax), b_lo, b_hi, float(lam), int(seed),
+                                        int(stream_id), _ptr(out), out.stride(0), _stream()), "mpq_noise_inject_sweep")
     return out
 
 

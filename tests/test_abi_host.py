@@ -127,6 +127,17 @@ def test_noise_validation():
 
 
 @needs_no_gpu
+def test_noise_sweep_validation():
+    f = mpq.lib().mpq_noise_inject_sweep
+    assert f(None, 4, 4, 0, FAKE, 2, 8, 0.5, 1, 2, FAKE, 16, None) == mpq.ERR_NULL
+    assert f(FAKE, 4, 4, 0, FAKE, 2, 8, 0.5, 1, 2, None, 16, None) == mpq.ERR_NULL
+    assert f(FAKE, 4, 4, 0, FAKE, 1, 8, 0.5, 1, 2, FAKE, 16, None) == mpq.ERR_BITS
+    assert f(FAKE, 4, 4, 0, FAKE, 5, 4, 0.5, 1, 2, FAKE, 16, None) == mpq.ERR_BITS
+    assert f(FAKE, 4, 4, 0, FAKE, 2, 8, 0.5, 1, 2, FAKE, 15, None) == mpq.ERR_SHAPE   # planes would overlap
+    assert f(FAKE, 4, 4, 3, FAKE, 2, 8, 0.5, 1, 2, FAKE, 16, None) == mpq.ERR_GRAN
+
+
+@needs_no_gpu
 def test_qgemm_validation():
     L = mpq.lib()
     f = L.mpq_qgemm

@@ -189,6 +189,26 @@ def test_noise_bit_exact(shape, gran):
             np.testing.assert_array_equal(got, want)
 
 
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("gran", GRANS)
+def test_noise_sweep_planes_equal_single_calls_bit_exact(shape, gran):
+    x = data(shape, 8)
+    am = oracle.absmax(x, gran)
+    t = torch()
+    for (b_lo, b_hi), lam, seed, sid in (((2, 8), 0.28867513, 7, 1), ((4, 5), 1.0, 0xDEADBEEFCAFEF00D, 2 ** 40 + 3)):
+        want = oracle.noise_inject_sweep(x, am, b_lo, b_hi, lam, seed, sid, gran)
+        nb = b_hi - b_lo + 1
+        for mk in (dev, dev_misaligned):
+            got = host(mpq.noise_inject_sweep(mk(x), dev(am), b_lo, b_hi, lam, seed, sid, gran))
+            np.testing.assert_array_equal(got, want)
+        # planes further apart than one tensor (and not a multiple of 4 elements apart)
+        buf = t.full((nb, x.size + 3), -1.0, dtype=t.float32, device="cuda")
+        out = buf[:, :x.size].view(nb, *x.shape) if False else buf.as_strided((nb,) + x.shape, (x.size + 3, x.shape[1], 1))
+        mpq.noise_inject_sweep(dev(x), dev(am), b_lo, b_hi, lam, seed, sid, gran, out=out)
+        np.testing.assert_array_equal(host(out), want)
+        assert (host(buf)[:, x.size:] == -1.0).all()   # the gaps between planes are left alone
+
+
 def test_noise_standard_normals_bit_exact_on_a_large_sample():
     n = 1 << 21
     zero = np.zeros((512, n // 512), np.float32)
