@@ -18,6 +18,7 @@ Other workloads (the parity-test configurations, measured with the same machiner
     cfg5  64 candidate bit configurations of a BERT-large FFN block at M = 16384, back to back,
           the output score taken in the second GEMM's epilogue (cfg5-unfused: qgemm + sse_pair)
     search  Alg. 1 / Alg. 2 over a 24-layer stack, evaluations per second
+    latency qgemm latency table at batch 1 and the mixed-precision latency estimate built from it
 All inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 """
 from __future__ import annotations
@@ -483,7 +484,7 @@ def run_search(torch, mpq, workloads, args):
     one read-back of the score.  Reports evaluations per second, eager and with one HIP graph per
     (layer, width)."""
     from paper_2302_01382_amd.stack import QuantStack
-    layers, width, rows, bits, target = 24, 1024, 4096, [8, 4, 2], 0.95
+    layers, width, rows, bits, target = 24, 1024, 4096, [8, 4, 2], 0.9
     x, weights = workloads.search_stack(seed=6, layers=layers, width=width, rows=rows)
     dx, dws = torch.from_numpy(x).cuda(), [torch.from_numpy(w).cuda() for w in weights]
     res = {}
@@ -502,9 +503,17 @@ def run_search(torch, mpq, workloads, args):
         torch.cuda.synchronize()
         t2 = time.perf_counter()
         res[mode] = {"greedy": {"evaluations": ev_g, "seconds": t1 - t0, "evaluations_per_s": ev_g / (t1 - t0),
-                                "mean_weight_bits": sum(cfg_g) / layers, "accuracy": st.evaluate(cfg_g)},
+                                "mean_weight_bits": sum(cfg_g) / layers, "accuracy": st.evaluate(cfg_g), "config": cfg_g},
                      "bisection": {"evaluations": ev_b, "seconds": t2 - t1, "evaluations_per_s": ev_b / (t2 - t1),
-                                   "mean_weight_bits": sum(cfg_b) / layers, "accuracy": st.evaluate(cfg_b)}}
+                                   "mean_weight_bits": sum(cfg_b) / layers, "accuracy": st.evaluate(cfg_b), "config": cfg_b}}
+    from paper_2302_01382_amd import latency as lat
+    shapes = [(rows, width, width)] * layers
+    table = lat.LatencyTable().measure(shapes[:1])
+    for mode in res:
+        for alg in ("greedy", "bisection"):
+            cfg = res[mode][alg].pop("config")
+            res[mode][alg]["estimated_relative_latency"] = round(table.relative(shapes, cfg), 4)
+            res[mode][alg]["relative_footprint"] = lat.relative_footprint(shapes, cfg)
     best = res["hip_graph_per_layer_and_width"]["greedy"]
     ops_per_eval = 2.0 * rows * width * width * layers
     out = {
@@ -522,12 +531,39 @@ def run_search(torch, mpq, workloads, args):
     print(json.dumps(out))
 
 
+def run_latency(torch, mpq, workloads, args):
+    """Kernel latency table of mpq_qgemm at inference batch size one (the configured ResNet-50 and
+    BERT-base layer shapes with M divided by their batch of 32) and the relative latency /
+    footprint it predicts for all-W4 against all-W8, the way the paper builds its latency columns."""
+    from paper_2302_01382_amd import latency as lat
+    groups = {"resnet50_batch1": [(g.M // 32, g.K, g.N) for g in workloads.CFG2],
+              "bert_base_seq384_batch1": [(g.M // 32, g.K, g.N) for g in workloads.CFG3]}
+    table = lat.LatencyTable()
+    out_groups = {}
+    for name, shapes in groups.items():
+        table.measure(shapes)
+        rows = [{"M": m, "K": k, "N": n, "w8_us": round(table.us[(m, k, n, 8)], 2), "w4_us": round(table.us[(m, k, n, 4)], 2)}
+                for (m, k, n) in shapes]
+        out_groups[name] = {"layers": rows,
+                            "all_w8_us": round(table.estimate_us(shapes, [8] * len(shapes)), 2),
+                            "all_w4_relative_latency": round(table.relative(shapes, [4] * len(shapes)), 4),
+                            "all_w4_relative_footprint": lat.relative_footprint(shapes, [4] * len(shapes))}
+    total = sum(v["all_w8_us"] for v in out_groups.values())
+    print(json.dumps({
+        "metric": "mpq_qgemm kernel latency table at batch 1 (microseconds) and the mixed-precision latency estimate",
+        "value": total, "unit": "us (all layers W8A8, both models)", "n_gpus": 1, "steps": 40, "warmup": 5,
+        "ms_per_step": total / 1e3, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8 x int8 -> int32 GEMM, fp32 epilogue", "data": "synthetic",
+        "config": {"workload": "latency: qgemm per layer shape and weight storage (int8 / packed int4), cold operands"},
+        "table": out_groups}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", choices=["cfg2", "cfg3", "cfg4", "cfg4-unfused", "cfg5", "cfg5-unfused", "search"], default="cfg2")
+    ap.add_argument("--workload", choices=["cfg2", "cfg3", "cfg4", "cfg4-unfused", "cfg5", "cfg5-unfused", "search", "latency"], default="cfg2")
     ap.add_argument("--cpu-sample-rows", type=int, default=1024)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -550,6 +586,9 @@ def main():
 
     if args.workload == "search":
         run_search(torch, mpq, workloads, args)
+        return
+    if args.workload == "latency":
+        run_latency(torch, mpq, workloads, args)
         return
     extra = {}
     traffic = None
