@@ -157,6 +157,30 @@ int mpq_qgemm_score(const int8_t* a_q, const void* w_q, int w_storage_bits, int6
                     const float* y_ref, double* sse_out, float* y_out, void* ws, size_t ws_bytes,
                     void* stream);
 
+/* ---- Sec. 3.1, second step ("adjustment"): the two scales of Eq. 1 as free parameters ---------
+ * In the integer form of this library the pair is inv (= alpha * levels, applied before rounding)
+ * and scale (= gamma / levels, applied after); calibration sets inv = qmax/m, scale = m/qmax.
+ * gran is MPQ_PER_TENSOR or MPQ_PER_ROW (else MPQ_ERR_GRAN); inv, scale: [1] or [rows].
+ *
+ * mpq_fake_quant_scales: code = clamp(RNE(x*inv), +-qmax) on the exact product, Q = fl32(code*scale);
+ *   y_out / codes_out nullable, at least one required.
+ * mpq_scale_grad: with g = dL/dQ (fp32 [rows x cols]) and rounding treated as the identity,
+ *   dscale_out[ch] = sum g*code,  dinv_out[ch] = scale[ch] * sum over elements whose rounded value
+ *   needs no clamping (|RNE(x*inv)| <= qmax) of g*x,  loss_out[ch] (nullable) = sum (Q - x)^2.
+ *   g == NULL selects the reconstruction loss L = sum (Q - x)^2 itself, g = 2 (Q - x).
+ *   fp32 per-lane partial sums, double from there on; outputs are doubles, 8-byte aligned.
+ *   Workspace: per-tensor granularity only (one partial triple per workgroup).
+ * mpq_scale_sgd_step: p[i] = fl32(p[i] - lr * dL/dp[i]) for both scale vectors, i < count, formed
+ *   in double and rounded once.  The model's own parameters are never touched. */
+int mpq_fake_quant_scales(const float* x, int64_t rows, int64_t cols, int gran, const float* inv,
+                          const float* scale, int bits, float* y_out, int8_t* codes_out, void* stream);
+size_t mpq_scale_grad_workspace_bytes(int64_t rows, int64_t cols, int gran);
+int mpq_scale_grad(const float* x, int64_t rows, int64_t cols, int gran, const float* inv,
+                   const float* scale, int bits, const float* g, double* dinv_out, double* dscale_out,
+                   double* loss_out, void* ws, size_t ws_bytes, void* stream);
+int mpq_scale_sgd_step(float* inv, float* scale, const double* dinv, const double* dscale,
+                       int64_t count, double lr, void* stream);
+
 /* ---- Alg. 1 (bisection search) and Alg. 2 (greedy search): host code ---------------------------
  * Both decide which per-layer bit configuration to evaluate next and return the final one; they
  * launch nothing themselves.  All pointers here are HOST pointers.

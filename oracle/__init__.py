@@ -215,3 +215,49 @@ def sse_pair(y, y_ref) -> float:
     r = np.ascontiguousarray(y_ref, dtype=np.float32).ravel()
     assert y.size == r.size
     return float(lib().orc_sse_pair(_p(y), _p(r), C.c_int64(y.size)))
+
+
+def fake_quant_scales(x, inv, scale, bits, gran=PER_TENSOR):
+    """Eq. 1 with explicit scales: returns (Q fp32, codes int8)."""
+    x = _f32_2d(x)
+    rows, cols = x.shape
+    inv = np.ascontiguousarray(inv, dtype=np.float32).ravel()
+    scale = np.ascontiguousarray(scale, dtype=np.float32).ravel()
+    assert inv.size == scale.size == _nch(gran, rows, cols)
+    y, codes = np.empty_like(x), np.empty(x.shape, np.int8)
+    _check(lib().orc_fake_quant_scales(_p(x), C.c_int64(rows), C.c_int64(cols), C.c_int(gran), _p(inv), _p(scale),
+                                       C.c_int(bits), _p(y), _p(codes)), "fake_quant_scales")
+    return y, codes
+
+
+def scale_grad(x, inv, scale, bits, g=None, gran=PER_TENSOR):
+    """Straight-through gradients of the two scales: returns dict(dinv, dscale, loss, abs_dinv,
+    abs_dscale), each float64 [nch]."""
+    x = _f32_2d(x)
+    rows, cols = x.shape
+    inv = np.ascontiguousarray(inv, dtype=np.float32).ravel()
+    scale = np.ascontiguousarray(scale, dtype=np.float32).ravel()
+    nch = _nch(gran, rows, cols)
+    assert inv.size == scale.size == nch
+    gp = None
+    if g is not None:
+        g = _f32_2d(g)
+        assert g.shape == x.shape
+        gp = _p(g)
+    out = {k: np.empty(nch, np.float64) for k in ("dinv", "dscale", "loss", "abs_dinv", "abs_dscale")}
+    _check(lib().orc_scale_grad(_p(x), C.c_int64(rows), C.c_int64(cols), C.c_int(gran), _p(inv), _p(scale),
+                                C.c_int(bits), gp, _p(out["dinv"]), _p(out["dscale"]), _p(out["loss"]),
+                                _p(out["abs_dinv"]), _p(out["abs_dscale"])), "scale_grad")
+    return out
+
+
+def scale_sgd_step(inv, scale, dinv, dscale, lr):
+    """Returns the updated (inv, scale) as new fp32 arrays."""
+    inv = np.array(inv, dtype=np.float32).ravel()
+    scale = np.array(scale, dtype=np.float32).ravel()
+    dinv = np.ascontiguousarray(dinv, dtype=np.float64).ravel()
+    dscale = np.ascontiguousarray(dscale, dtype=np.float64).ravel()
+    assert inv.size == scale.size == dinv.size == dscale.size
+    _check(lib().orc_scale_sgd_step(_p(inv), _p(scale), _p(dinv), _p(dscale), C.c_int64(inv.size), C.c_double(lr)),
+           "scale_sgd_step")
+    return inv, scale

@@ -20,6 +20,9 @@
 //   orc_qgemm           Alg. 1 / Alg. 2 "Evaluate f(x, w)": one linear layer with both operands
 //                       quantized; integer contraction, floating-point rescale.
 //   orc_sse_pair        Alg. 1 / Alg. 2 "save accuracy a": stand-in score, squared output error.
+//   orc_fake_quant_scales, orc_scale_grad, orc_scale_sgd_step
+//                       Sec. 3.1, adjustment step: Eq. 1 with its two scales as free parameters,
+//                       their straight-through gradients, one gradient-descent step on them.
 //
 // Parity status: every function here is pinned by tests (brute force, exact rational arithmetic,
 // closed forms, invariants, published Philox known-answer vectors).  Nothing is "parity unpinned".
@@ -354,6 +357,86 @@ double orc_sse_pair(const float* y, const float* y_ref, int64_t n) {
     s += d * d;
   }
   return s;
+}
+
+// ------------------------------------------------------------------------------------------
+// Sec. 3.1, second step ("adjustment"): after calibration the two scales of Eq. 1 are free
+// parameters, here as the pair the integer form works with: inv (= alpha * levels, applied
+// before rounding) and scale (= gamma / levels, applied after).
+//
+// Forward with explicit scales: code = clamp(RNE(x * inv), +-qmax) on the exact product,
+// Q = fl32(code * scale).
+int orc_fake_quant_scales(const float* x, int64_t rows, int64_t cols, int gran, const float* inv,
+                          const float* scale, int bits, float* y, int8_t* codes) {
+  if (!x || !inv || !scale || rows <= 0 || cols <= 0 || gran < 0 || gran > 1) return ORC_BAD_ARG;
+  if (bits < 2 || bits > 8) return ORC_BAD_ARG;
+  if (std::fegetround() != FE_TONEAREST) return ORC_BAD_ARG;
+  const int qmax = orc_qmax(bits);
+  for (int64_t r = 0; r < rows; ++r)
+    for (int64_t c = 0; c < cols; ++c) {
+      const int64_t ch = channel_of(gran, r, c), i = r * cols + c;
+      const int q = code_of(x[i], inv[ch], qmax);
+      if (y) y[i] = dequant_of(q, scale[ch]);
+      if (codes) codes[i] = (int8_t)q;
+    }
+  return ORC_OK;
+}
+
+// Gradients of a loss L with respect to the two scales, rounding treated as the identity
+// (straight-through): with g_i = dL/dQ_i,
+//   dL/dscale = sum_i g_i * code_i                       (Q is linear in scale: exact)
+//   dL/dinv   = scale * sum_{i not clipped} g_i * x_i    (d clip(u)/du = 1 where the clamp of the
+//               rounded value is inactive, |RNE(x inv)| <= qmax, else 0)
+// g == null selects the reconstruction loss L = sum (Q - x)^2 with Q = code * scale taken exactly,
+// g_i = 2 (Q_i - x_i).  loss is that sum of squares in either case.  abs_* (nullable) receive the
+// sums of the absolute values of the terms, the natural yardstick for an error bound.
+// All outputs are per channel, accumulated in double in index order.
+int orc_scale_grad(const float* x, int64_t rows, int64_t cols, int gran, const float* inv,
+                   const float* scale, int bits, const float* g, double* dinv, double* dscale,
+                   double* loss, double* abs_dinv, double* abs_dscale) {
+  if (!x || !inv || !scale || !dinv || !dscale || rows <= 0 || cols <= 0 || gran < 0 || gran > 1)
+    return ORC_BAD_ARG;
+  if (bits < 2 || bits > 8) return ORC_BAD_ARG;
+  if (std::fegetround() != FE_TONEAREST) return ORC_BAD_ARG;
+  const int qmax = orc_qmax(bits);
+  const int64_t nch = channel_count(gran, rows, cols);
+  std::vector<double> sx(nch, 0.0), sq(nch, 0.0), sl(nch, 0.0), ax(nch, 0.0), aq(nch, 0.0);
+  for (int64_t r = 0; r < rows; ++r)
+    for (int64_t c = 0; c < cols; ++c) {
+      const int64_t ch = channel_of(gran, r, c), i = r * cols + c;
+      const double rounded = std::nearbyint((double)x[i] * (double)inv[ch]);
+      const bool clipped = std::fabs(rounded) > (double)qmax;
+      const int q = code_of(x[i], inv[ch], qmax);
+      const double e = (double)q * (double)scale[ch] - (double)x[i];
+      const double gi = g ? (double)g[i] : 2.0 * e;
+      sq[ch] += gi * (double)q;
+      aq[ch] += std::fabs(gi * (double)q);
+      if (!clipped) {
+        sx[ch] += gi * (double)x[i];
+        ax[ch] += std::fabs(gi * (double)x[i]);
+      }
+      sl[ch] += e * e;
+    }
+  for (int64_t ch = 0; ch < nch; ++ch) {
+    dscale[ch] = sq[ch];
+    dinv[ch] = (double)scale[ch] * sx[ch];
+    if (loss) loss[ch] = sl[ch];
+    if (abs_dscale) abs_dscale[ch] = aq[ch];
+    if (abs_dinv) abs_dinv[ch] = std::fabs((double)scale[ch]) * ax[ch];
+  }
+  return ORC_OK;
+}
+
+// One step of plain gradient descent on the scales only (the model's parameters stay as they
+// are): p <- fl32(p - lr * dL/dp), formed in double and rounded once.
+int orc_scale_sgd_step(float* inv, float* scale, const double* dinv, const double* dscale,
+                       int64_t count, double lr) {
+  if (!inv || !scale || !dinv || !dscale || count <= 0) return ORC_BAD_ARG;
+  for (int64_t i = 0; i < count; ++i) {
+    inv[i] = (float)((double)inv[i] - lr * dinv[i]);
+    scale[i] = (float)((double)scale[i] - lr * dscale[i]);
+  }
+  return ORC_OK;
 }
 
 }  // extern "C"

@@ -23,6 +23,7 @@ EXPORTS = [
     "mpq_quant_error", "mpq_noise_inject", "mpq_qgemm_workspace_bytes", "mpq_qgemm",
     "mpq_sse_pair_workspace_bytes", "mpq_sse_pair", "mpq_qgemm_score_workspace_bytes", "mpq_qgemm_score",
     "mpq_search_bisection", "mpq_search_greedy", "mpq_noise_inject_sweep",
+    "mpq_fake_quant_scales", "mpq_scale_grad_workspace_bytes", "mpq_scale_grad", "mpq_scale_sgd_step",
 ]
 
 EVAL_FN = C.CFUNCTYPE(C.c_double, C.POINTER(C.c_int), C.c_int, C.c_void_p)
@@ -63,6 +64,11 @@ def lib():
         L.mpq_quant_error.argtypes = [vp, i64, i64, ci, vp, ci, ci, vp, vp, sz, vp]
         L.mpq_noise_inject.argtypes = [vp, i64, i64, ci, vp, ci, C.c_float, C.c_uint64, C.c_uint64, vp, vp]
         L.mpq_noise_inject_sweep.argtypes = [vp, i64, i64, ci, vp, ci, ci, C.c_float, C.c_uint64, C.c_uint64, vp, i64, vp]
+        L.mpq_fake_quant_scales.argtypes = [vp, i64, i64, ci, vp, vp, ci, vp, vp, vp]
+        L.mpq_scale_grad_workspace_bytes.restype = sz
+        L.mpq_scale_grad_workspace_bytes.argtypes = [i64, i64, ci]
+        L.mpq_scale_grad.argtypes = [vp, i64, i64, ci, vp, vp, ci, vp, vp, vp, vp, vp, sz, vp]
+        L.mpq_scale_sgd_step.argtypes = [vp, vp, vp, vp, i64, C.c_double, vp]
         L.mpq_qgemm_workspace_bytes.restype = sz
         L.mpq_qgemm_workspace_bytes.argtypes = [i64, i64, i64, ci]
         L.mpq_qgemm.argtypes = [vp, vp, ci, i64, i64, i64, vp, vp, ci, vp, vp, vp, sz, vp]
@@ -316,3 +322,46 @@ def search_bisection(order, bit_widths, target, evaluate, ensure_target=False):
 def search_greedy(order, bit_widths, target, evaluate):
     """Alg. 2.  Same arguments and result as search_bisection."""
     return _search(lib().mpq_search_greedy, "mpq_search_greedy", order, bit_widths, target, evaluate, 0)
+
+
+def fake_quant_scales(x, inv, scale, bits, gran=PER_TENSOR, want_y=True, want_codes=False):
+    """Eq. 1 with explicit scales (after adjustment they no longer derive from one absmax)."""
+    torch = _torch()
+    x = _dev2d(x, torch.float32)
+    rows, cols = x.shape
+    y = torch.empty_like(x) if want_y else None
+    codes = torch.empty((rows, cols), dtype=torch.int8, device=x.device) if want_codes else None
+    _check(lib().mpq_fake_quant_scales(_ptr(x), rows, cols, gran, _ptr(inv), _ptr(scale), bits, _ptr(y), _ptr(codes),
+                                       _stream()), "mpq_fake_quant_scales")
+    return y, codes
+
+
+def scale_grad_workspace_bytes(rows, cols, gran=PER_TENSOR) -> int:
+    return int(lib().mpq_scale_grad_workspace_bytes(rows, cols, gran))
+
+
+def scale_grad(x, inv, scale, bits, g=None, gran=PER_TENSOR, ws: Workspace = None):
+    """Straight-through gradients of the two scales.  Returns (dinv, dscale, loss), float64 [nch]."""
+    torch = _torch()
+    x = _dev2d(x, torch.float32)
+    rows, cols = x.shape
+    nch = _nch(gran, rows, cols)
+    if g is not None:
+        g = _dev2d(g, torch.float32)
+        if g.shape != x.shape:
+            raise ValueError("the upstream gradient must have the tensor's shape")
+    out = [torch.empty(nch, dtype=torch.float64, device=x.device) for _ in range(3)]
+    wp, wn = (ws or _default_ws).get(scale_grad_workspace_bytes(rows, cols, gran))
+    _check(lib().mpq_scale_grad(_ptr(x), rows, cols, gran, _ptr(inv), _ptr(scale), bits, _ptr(g), _ptr(out[0]),
+                                _ptr(out[1]), _ptr(out[2]), wp, wn, _stream()), "mpq_scale_grad")
+    return tuple(out)
+
+
+def scale_sgd_step(inv, scale, dinv, dscale, lr):
+    """In place: inv -= lr * dinv, scale -= lr * dscale (double arithmetic, one rounding)."""
+    n = inv.numel()
+    if not (scale.numel() == dinv.numel() == dscale.numel() == n):
+        raise ValueError("scale vectors and gradients must have one entry per channel")
+    _check(lib().mpq_scale_sgd_step(_ptr(inv), _ptr(scale), _ptr(dinv), _ptr(dscale), n, float(lr), _stream()),
+           "mpq_scale_sgd_step")
+    return inv, scale

@@ -183,6 +183,24 @@ def test_qgemm_score_validation():
     assert f(FAKE16, FAKE16, 8, 256, 256, 64, None, FAKE, 0, FAKE16, FAKE16, None, FAKE16, need, None) == mpq.ERR_NULL
 
 
+@needs_no_gpu
+def test_scale_adjust_validation():
+    L = mpq.lib()
+    assert L.mpq_scale_grad_workspace_bytes(64, 64, 0) > 0
+    assert L.mpq_scale_grad_workspace_bytes(64, 64, 1) == 0      # per row: results are written directly
+    fq, sg, st = L.mpq_fake_quant_scales, L.mpq_scale_grad, L.mpq_scale_sgd_step
+    assert fq(FAKE, 4, 4, 0, FAKE, FAKE, 4, None, None, None) == mpq.ERR_NULL
+    assert fq(FAKE, 4, 4, 2, FAKE, FAKE, 4, FAKE, None, None) == mpq.ERR_GRAN   # per column is not offered
+    assert fq(FAKE, 4, 4, 0, FAKE, FAKE, 9, FAKE, None, None) == mpq.ERR_BITS
+    need = L.mpq_scale_grad_workspace_bytes(64, 64, 0)
+    assert sg(FAKE16, 64, 64, 0, FAKE, FAKE, 4, None, None, FAKE16, None, FAKE16, need, None) == mpq.ERR_NULL
+    assert sg(FAKE16, 64, 64, 0, FAKE, FAKE, 4, None, FAKE16, FAKE16, None, None, 0, None) == mpq.ERR_WORKSPACE
+    assert sg(FAKE16, 64, 64, 0, FAKE, FAKE, 4, None, C.c_void_p(0x10004), FAKE16, None, FAKE16, need, None) == mpq.ERR_ALIGN
+    assert sg(FAKE16, 0, 64, 0, FAKE, FAKE, 4, None, FAKE16, FAKE16, None, FAKE16, need, None) == mpq.ERR_SHAPE
+    assert st(None, FAKE, FAKE, FAKE, 4, 1e-5, None) == mpq.ERR_NULL
+    assert st(FAKE, FAKE, FAKE, FAKE, 0, 1e-5, None) == mpq.ERR_SHAPE
+
+
 def test_python_errors_carry_the_message():
     with pytest.raises(mpq.MpqError) as e:
         mpq._check(mpq.ERR_BITS, "mpq_fake_quant")
