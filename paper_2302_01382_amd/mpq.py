@@ -48,6 +48,12 @@ def lib():
         path = _build.LIB
         if not os.path.exists(path):
             _build.build_lib()
+        # torch ships its own HIP runtime; whichever copy is loaded first serves the whole process,
+        # and device buffers made by torch must belong to the runtime that launches the kernels
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = C.CDLL(path)
         vp, i64, ci, sz = C.c_void_p, C.c_int64, C.c_int, C.c_size_t
         L.mpq_strerror.restype = C.c_char_p
