@@ -379,7 +379,6 @@ def workload_cfg5(torch, P, workloads, fused):
     cw1, pw1 = torch.empty((N1, K1), dtype=i8, device=dev), torch.empty((N1, K1 // 2), dtype=u8, device=dev)
     cw2, pw2 = torch.empty((N2, N1), dtype=i8, device=dev), torch.empty((N2, N1 // 2), dtype=u8, device=dev)
     h = torch.empty((M, N1), dtype=f32, device=dev)
-    g = torch.empty((M, N1), dtype=f32, device=dev)
     y = torch.empty((M, N2), dtype=f32, device=dev)
     scores = torch.empty(len(cands), dtype=f64, device=dev)
     ws = P.Workspace()
@@ -407,11 +406,11 @@ def workload_cfg5(torch, P, workloads, fused):
             P.scale_from_absmax(am_x, ba1, out=s[2])
             with rec("qgemm", M * K1 + N1 * K1 * st1 // 8 + 4 * M * N1, 2 * M * N1 * K1):
                 P.qgemm(cx, q1, s[2], s[0], st1, y=h, ws=ws)
-            g.copy_(gelu(h))  # the activation is not a libmpq call: torch, on the same stream
-            with rec("absmax", 4 * g.numel()):
-                P.calibrate_absmax(g, out=am_h, ws=ws)
-            with rec("fake_quant", 5 * g.numel()):
-                P.fake_quant(g, am_h, ba2, want_y=False, codes=ch)
+            torch.ops.aten.gelu_(h)  # the activation is not a libmpq call: torch, in place, same stream
+            with rec("absmax", 4 * h.numel()):
+                P.calibrate_absmax(h, out=am_h, ws=ws)
+            with rec("fake_quant", 5 * h.numel()):
+                P.fake_quant(h, am_h, ba2, want_y=False, codes=ch)
             P.scale_from_absmax(am_h, ba2, out=s[3])
             if fused:  # the score is taken in the epilogue: Y_ref is read, Y is never written
                 with rec("qgemm", M * N1 + N2 * N1 * st2 // 8 + 4 * M * N2, 2 * M * N2 * N1):
