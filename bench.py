@@ -373,7 +373,11 @@ def workload_cfg5(torch, P, workloads, fused):
     y_ref = gelu(dx @ dw1.t()) @ dw2.t()
     am_x, am_h = torch.empty(1, dtype=f32, device=dev), torch.empty(1, dtype=f32, device=dev)
     am_w1, am_w2 = torch.empty(1, dtype=f32, device=dev), torch.empty(1, dtype=f32, device=dev)
-    s = [torch.empty(1, dtype=f32, device=dev) for _ in range(4)]
+    s_h = torch.empty(1, dtype=f32, device=dev)
+    # step sizes of the tensors whose absmax does not change from candidate to candidate, per width
+    s_w1 = {b: torch.empty(1, dtype=f32, device=dev) for b in (2, 4, 8)}
+    s_w2 = {b: torch.empty(1, dtype=f32, device=dev) for b in (2, 4, 8)}
+    s_x = {b: torch.empty(1, dtype=f32, device=dev) for b in (4, 8)}
     cx = torch.empty((M, K1), dtype=i8, device=dev)
     ch = torch.empty((M, N1), dtype=i8, device=dev)
     cw1, pw1 = torch.empty((N1, K1), dtype=i8, device=dev), torch.empty((N1, K1 // 2), dtype=u8, device=dev)
@@ -384,13 +388,12 @@ def workload_cfg5(torch, P, workloads, fused):
     ws = P.Workspace()
     ws.get(1 << 22)
 
-    def quant_w(rec, dw, am, b, codes, packed, sc):
+    def quant_w(rec, dw, am, b, codes, packed):
         with rec("fake_quant", int(dw.numel() * (4.5 if b <= 4 else 5))):
             if b <= 4:
                 P.fake_quant(dw, am, b, want_y=False, packed4=packed)
             else:
                 P.fake_quant(dw, am, b, want_y=False, codes=codes)
-        P.scale_from_absmax(am, b, out=sc)
         return (packed, 4) if b <= 4 else (codes, 8)
 
     def step(rec):
@@ -398,26 +401,30 @@ def workload_cfg5(torch, P, workloads, fused):
             P.calibrate_absmax(dx, out=am_x, ws=ws)
             P.calibrate_absmax(dw1, out=am_w1, ws=ws)
             P.calibrate_absmax(dw2, out=am_w2, ws=ws)
+        for b in (2, 4, 8):
+            P.scale_from_absmax(am_w1, b, out=s_w1[b])
+            P.scale_from_absmax(am_w2, b, out=s_w2[b])
+        for b in (4, 8):
+            P.scale_from_absmax(am_x, b, out=s_x[b])
         for c, (bw1, ba1, bw2, ba2) in enumerate(cands):
-            q1, st1 = quant_w(rec, dw1, am_w1, bw1, cw1, pw1, s[0])
-            q2, st2 = quant_w(rec, dw2, am_w2, bw2, cw2, pw2, s[1])
+            q1, st1 = quant_w(rec, dw1, am_w1, bw1, cw1, pw1)
+            q2, st2 = quant_w(rec, dw2, am_w2, bw2, cw2, pw2)
             with rec("fake_quant", 5 * dx.numel()):
                 P.fake_quant(dx, am_x, ba1, want_y=False, codes=cx)
-            P.scale_from_absmax(am_x, ba1, out=s[2])
             with rec("qgemm", M * K1 + N1 * K1 * st1 // 8 + 4 * M * N1, 2 * M * N1 * K1):
-                P.qgemm(cx, q1, s[2], s[0], st1, y=h, ws=ws)
+                P.qgemm(cx, q1, s_x[ba1], s_w1[bw1], st1, y=h, ws=ws)
             torch.ops.aten.gelu_(h)  # the activation is not a libmpq call: torch, in place, same stream
             with rec("absmax", 4 * h.numel()):
                 P.calibrate_absmax(h, out=am_h, ws=ws)
             with rec("fake_quant", 5 * h.numel()):
                 P.fake_quant(h, am_h, ba2, want_y=False, codes=ch)
-            P.scale_from_absmax(am_h, ba2, out=s[3])
+            P.scale_from_absmax(am_h, ba2, out=s_h)
             if fused:  # the score is taken in the epilogue: Y_ref is read, Y is never written
                 with rec("qgemm", M * N1 + N2 * N1 * st2 // 8 + 4 * M * N2, 2 * M * N2 * N1):
-                    P.qgemm_score(ch, q2, s[3], s[1], y_ref, st2, out=scores[c:c + 1], ws=ws)
+                    P.qgemm_score(ch, q2, s_h, s_w2[bw2], y_ref, st2, out=scores[c:c + 1], ws=ws)
             else:
                 with rec("qgemm", M * N1 + N2 * N1 * st2 // 8 + 4 * M * N2, 2 * M * N2 * N1):
-                    P.qgemm(ch, q2, s[3], s[1], st2, y=y, ws=ws)
+                    P.qgemm(ch, q2, s_h, s_w2[bw2], st2, y=y, ws=ws)
                 with rec("sse_pair", 8 * y.numel()):
                     P.sse_pair(y, y_ref, out=scores[c:c + 1], ws=ws)
 
