@@ -15,8 +15,9 @@ Other workloads (the parity-test configurations, measured with the same machiner
     cfg4  sensitivity sweep over the 96 BERT-large weight tensors: absmax + quant_error per tensor
           and per output channel, noise at every b = 2..8 from one call per tensor
           (cfg4-unfused: one call per granularity and per noise level)
-    cfg5  64 candidate bit configurations of a BERT-large FFN block at M = 16384, back to back,
-          the output score taken in the second GEMM's epilogue (cfg5-unfused: qgemm + sse_pair)
+    cfg5  64 candidate bit configurations of a BERT-large FFN block at M = 16384, back to back;
+          GELU and the calibration of its output in the first GEMM's epilogue, the output score in
+          the second's (cfg5-unfused: mpq_qgemm, torch GELU, mpq_calibrate_absmax, mpq_sse_pair)
     search  Alg. 1 / Alg. 2 over a 24-layer stack, evaluations per second
     latency qgemm latency table at batch 1 and the mixed-precision latency estimate built from it
 All inputs are resident in HBM before the timed region.  Prints ONE JSON line.
@@ -411,11 +412,15 @@ def workload_cfg5(torch, P, workloads, fused):
             q2, st2 = quant_w(rec, dw2, am_w2, bw2, cw2, pw2)
             with rec("fake_quant", 5 * dx.numel()):
                 P.fake_quant(dx, am_x, ba1, want_y=False, codes=cx)
-            with rec("qgemm", M * K1 + N1 * K1 * st1 // 8 + 4 * M * N1, 2 * M * N1 * K1):
-                P.qgemm(cx, q1, s_x[ba1], s_w1[bw1], st1, y=h, ws=ws)
-            torch.ops.aten.gelu_(h)  # the activation is not a libmpq call: torch, in place, same stream
-            with rec("absmax", 4 * h.numel()):
-                P.calibrate_absmax(h, out=am_h, ws=ws)
+            if fused:  # GELU and the calibration of its output happen in the first GEMM's epilogue
+                with rec("qgemm", M * K1 + N1 * K1 * st1 // 8 + 4 * M * N1, 2 * M * N1 * K1):
+                    P.qgemm_act(cx, q1, s_x[ba1], s_w1[bw1], P.ACT_GELU, st1, y=h, absmax=am_h)
+            else:
+                with rec("qgemm", M * K1 + N1 * K1 * st1 // 8 + 4 * M * N1, 2 * M * N1 * K1):
+                    P.qgemm(cx, q1, s_x[ba1], s_w1[bw1], st1, y=h, ws=ws)
+                torch.ops.aten.gelu_(h)  # torch, in place, same stream
+                with rec("absmax", 4 * h.numel()):
+                    P.calibrate_absmax(h, out=am_h, ws=ws)
             with rec("fake_quant", 5 * h.numel()):
                 P.fake_quant(h, am_h, ba2, want_y=False, codes=ch)
             P.scale_from_absmax(am_h, ba2, out=s_h)
@@ -432,12 +437,14 @@ def workload_cfg5(torch, P, workloads, fused):
         return [scores.clone()]
 
     per_cand = (4.75 * (dw1.numel() + dw2.numel()) + 5 * dx.numel() + (M * K1 + N1 * K1 + 4 * M * N1)
-                + 4 * M * N1 + 5 * M * N1 + (M * N1 + N2 * N1 + 4 * M * N2) + (0 if fused else 8 * M * N2))
+                + (0 if fused else 4 * M * N1) + 5 * M * N1 + (M * N1 + N2 * N1 + 4 * M * N2)
+                + (0 if fused else 8 * M * N2))
     nbytes = int(len(cands) * per_cand + 4 * (dx.numel() + dw1.numel() + dw2.numel()))
     ops = len(cands) * (2 * M * N1 * K1 + 2 * M * N2 * N1)
     label = ("cfg5: 64 candidate bit configurations of a BERT-large FFN block (1024 -> 4096 -> 1024) at "
-             "M = 16384, back to back: re-quantize, qgemm, GELU (torch), re-quantize, qgemm, output SSE"
-             + (" taken in the second GEMM's epilogue" if fused else " in a pass of its own"))
+             "M = 16384, back to back: re-quantize, qgemm, GELU, calibrate, re-quantize, qgemm, output SSE"
+             + ("; GELU + calibration in the first GEMM's epilogue, the score in the second's" if fused
+                else "; GELU by torch, calibration and score as passes of their own"))
     return step, snapshot, nbytes, ops, label, len(cands)
 
 

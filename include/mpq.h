@@ -142,6 +142,21 @@ size_t mpq_sse_pair_workspace_bytes(int64_t n);
 int mpq_sse_pair(const float* y, const float* y_ref, int64_t n, double* sse_out, void* ws,
                  size_t ws_bytes, void* stream);
 
+/* ---- the layer of mpq_qgemm with what follows it in "Evaluate f(x, w)" taken in its epilogue ----
+ * y_out = act(Y) with Y as mpq_qgemm defines it, act one of mpq_act:
+ *   MPQ_ACT_RELU  max(Y, 0);   MPQ_ACT_GELU  Y * Phi(Y), evaluated as Y/2 * (1 + erf(Y / sqrt 2))
+ *   in fp32: within 1e-5 relative of the exact value, or 2e-7 |Y| where that is larger (the
+ *   negative tail, where GELU is below 1e-4 |Y|).
+ * absmax_out nullable float[1]: max |y_out|, i.e. the max calibration (Sec. 3.1) of the next
+ *   layer's input, taken on the values while they are in registers.  accumulate = 0 overwrites
+ *   it, 1 keeps a running maximum (absmax_out must then hold a valid non-negative value).
+ *   The maximum is exact (order independent).  y_out is required; other arguments and errors as
+ *   mpq_qgemm, plus MPQ_ERR_SHAPE for an unknown act.  No workspace. */
+enum mpq_act { MPQ_ACT_NONE = 0, MPQ_ACT_RELU = 1, MPQ_ACT_GELU = 2 };
+int mpq_qgemm_act(const int8_t* a_q, const void* w_q, int w_storage_bits, int64_t M, int64_t N,
+                  int64_t K, const float* a_scale, const float* w_scale, int w_gran, int act,
+                  float* y_out, float* absmax_out, int accumulate, void* stream);
+
 /* ---- "Evaluate f(x, w) and save accuracy a" of Alg. 1 / Alg. 2 in one call -------------------
  * The layer of mpq_qgemm with the score of mpq_sse_pair taken in its epilogue:
  * sse_out[0] = sum_{m,n} (y[m][n] - y_ref[m][n])^2 (double), y exactly as mpq_qgemm defines it.

@@ -261,3 +261,21 @@ def scale_sgd_step(inv, scale, dinv, dscale, lr):
     _check(lib().orc_scale_sgd_step(_p(inv), _p(scale), _p(dinv), _p(dscale), C.c_int64(inv.size), C.c_double(lr)),
            "scale_sgd_step")
     return inv, scale
+
+
+ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
+
+
+def activation(y, act):
+    """ReLU or exact-Phi GELU of an fp32 array (a new array)."""
+    out = np.array(y, dtype=np.float32, order="C")
+    _check(lib().orc_activation(_p(out), C.c_int64(out.size), C.c_int(act)), "activation")
+    return out
+
+
+def qgemm_act(a_q, w_q, a_scale, w_scale, act, w_storage_bits=8, w_gran=PER_TENSOR):
+    """The layer followed by its activation, and the absmax of the result: by definition the
+    composition of qgemm, activation and absmax.  Returns (y, absmax float32[1])."""
+    y, _ = qgemm(a_q, w_q, a_scale, w_scale, w_storage_bits, w_gran)
+    y = activation(y, act)
+    return y, absmax(y)

@@ -349,6 +349,19 @@ int orc_qgemm(const int8_t* a_q, const void* w_q, int w_storage_bits, int64_t M,
   return ORC_OK;
 }
 
+// Activations a layer may be followed by inside "Evaluate f(x, w)": ReLU, or GELU(x) = x Phi(x)
+// with the exact Gaussian distribution function, evaluated in double and rounded to fp32 once.
+// act: 0 none, 1 ReLU, 2 GELU.  In place.
+int orc_activation(float* y, int64_t n, int act) {
+  if (!y || n <= 0 || act < 0 || act > 2) return ORC_BAD_ARG;
+  for (int64_t i = 0; i < n; ++i) {
+    const double x = (double)y[i];
+    if (act == 1) y[i] = x > 0.0 ? y[i] : 0.0f;
+    else if (act == 2) y[i] = (float)(0.5 * x * std::erfc(-x / std::sqrt(2.0)));
+  }
+  return ORC_OK;
+}
+
 // Squared distance between two tensors, in double, index order.
 double orc_sse_pair(const float* y, const float* y_ref, int64_t n) {
   double s = 0.0;

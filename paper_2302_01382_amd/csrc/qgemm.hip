@@ -22,6 +22,30 @@ namespace mpq {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
+// What an epilogue may do beyond Y = (float(acc) * s_A) * s_W[n]:
+//  - score: accumulate sum (Y - yref)^2, one double partial per workgroup in `part`;
+//  - activation: Y <- act(Y) before it is stored (1 = ReLU, 2 = GELU), and the largest |Y| after
+//    the activation merged into amax[0] (an integer atomic max over the bit patterns of the
+//    non-negative floats: exact and independent of the order).
+struct EpiArgs {
+  const float* yref;
+  double* part;
+  int act;
+  unsigned* amax;
+};
+
+// GELU(x) = x Phi(x) = x/2 * (1 + erf(x / sqrt 2)).  The sum cancels in the negative tail, so the
+// error there is absolute, about 1e-7 |x| (GELU itself is below 1e-4 |x| beyond x = -3.7); the
+// erfc form would be accurate to the last bit there too, but costs three times the arithmetic, and
+// the epilogue's arithmetic is not hidden behind anything.
+__device__ __forceinline__ float apply_act(float y, int act) {
+  if (act == 1) return fmaxf(y, 0.0f);
+  if (act == 2) return (0.5f * y) * (1.0f + erff(y * 0.70710678118654752f));
+  return y;
+}
+
+__global__ void fill_u32_k(unsigned* p, unsigned v) { p[0] = v; }
+
 constexpr int BM = 128, BN = 128, BK = 64;  // block tile; BK in bytes of k
 constexpr int kGemmThreads = 256;           // 4 waves as 2 x 2, each 64 x 64 = 2 x 2 MFMA tiles
 
@@ -117,9 +141,9 @@ __global__ __launch_bounds__(kGemmThreads) void qgemm_k(const int8_t* __restrict
                                                         const float* __restrict__ a_scale,
                                                         const float* __restrict__ w_scale,
                                                         int w_per_row, float* __restrict__ Y,
-                                                        int32_t* __restrict__ ACC,
-                                                        const float* __restrict__ YREF,
-                                                        double* __restrict__ PART) {
+                                                        int32_t* __restrict__ ACC, EpiArgs epi) {
+  const float* __restrict__ YREF = epi.yref;
+  double* __restrict__ PART = epi.part;
   __shared__ __attribute__((aligned(16))) int8_t lds_a[BM * BK];
   __shared__ __attribute__((aligned(16))) int8_t lds_b[BN * BK];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -173,6 +197,7 @@ __global__ __launch_bounds__(kGemmThreads) void qgemm_k(const int8_t* __restrict
   const bool want_y = Y || YREF;
   const float sa = want_y ? a_scale[0] : 0.0f;
   float sse = 0.0f;  // this lane's share of sum (Y - YREF)^2
+  float amax = 0.0f;
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
     const int64_t n = n0 + wn * 64 + j * 32 + (lane & 31);
@@ -187,7 +212,8 @@ __global__ __launch_bounds__(kGemmThreads) void qgemm_k(const int8_t* __restrict
         int a = acc[i][j][v];
         if (W4) a >>= 4;  // exact: every product carried the factor 16
         if (ACC) ACC[m * N + n] = a;
-        const float y = ((float)a * sa) * sw;
+        const float y = apply_act(((float)a * sa) * sw, epi.act);
+        amax = fmaxf(amax, fabsf(y));
         if (Y) Y[m * N + n] = y;
         if (YREF) {
           const float d = y - YREF[m * N + n];
@@ -204,6 +230,10 @@ __global__ __launch_bounds__(kGemmThreads) void qgemm_k(const int8_t* __restrict
     __syncthreads();
     if (threadIdx.x == 0)
       PART[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = ((double)sm[0] + (double)sm[1]) + ((double)sm[2] + (double)sm[3]);
+  }
+  if (epi.amax) {
+    const float w = wave_max(amax);
+    if (lane == 0) atomicMax(epi.amax, abs_key(w));
   }
 }
 
@@ -505,19 +535,21 @@ __device__ __forceinline__ void k_substep(v16i (&acc)[C::FM][C::FN], const v4i (
 // that a tile always starts in stage 0.)  Chunks stay short so that the hardware dispatcher, not a
 // fixed assignment, balances the load when other kernels hold some of the CUs.
 // MINW: waves the register allocation must leave room for on one SIMD.
-// SCORE: also accumulate sum (Y - YREF)^2, one partial per workgroup (a variant of its own: the
-// largest tile has no registers to spare for it in the plain kernel).
-template <int BM, int BN, int WM, int WN, int NSTAGE, bool W4, bool VEC, int KB, int MINW, bool SCORE>
+// EPI: 0 plain, 1 score, 2 activation and absmax of the output (see EpiArgs); variants of their
+// own because the largest tile has no registers to spare for them in the plain kernel.
+template <int BM, int BN, int WM, int WN, int NSTAGE, bool W4, bool VEC, int KB, int MINW, int EPI>
 __global__ __launch_bounds__(WM * WN * 64, MINW) void qgemm_dma(const int8_t* __restrict__ A,
                                                           const void* __restrict__ Wv, int64_t M,
                                                           int64_t N, int64_t K,
                                                           const float* __restrict__ a_scale,
                                                           const float* __restrict__ w_scale,
                                                           int w_per_row, float* __restrict__ Y,
-                                                          int32_t* __restrict__ ACC,
-                                                          const float* __restrict__ YREF,
-                                                          double* __restrict__ PART, int tiles_n,
-                                                          int tiles_m, int chunk, int remap) {
+                                                          int32_t* __restrict__ ACC, EpiArgs epi,
+                                                          int tiles_n, int tiles_m, int chunk,
+                                                          int remap) {
+  constexpr bool SCORE = EPI == 1, ACT = EPI == 2;
+  const float* __restrict__ YREF = epi.yref;
+  double* __restrict__ PART = epi.part;
   using C = DmaCfg<BM, BN, WM, WN, NSTAGE, W4, KB>;
   constexpr int DBK = KB;
   constexpr int NSUB = DBK / 32;
@@ -578,6 +610,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void qgemm_dma(const int8_t* __
     for (int j = 0; j < C::FN; ++j) load_b_frag<C, W4>(pb, j, fb[j]);
   }
   float sse = 0.0f;    // this lane's share of sum (Y - YREF)^2 over the chunk
+  float amax = 0.0f;   // this lane's largest |Y| after the activation
   bool drain = false;  // true for the first wait after an epilogue: stores are in flight, and
                        // loads and stores do not retire in order with respect to each other
 
@@ -654,8 +687,13 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void qgemm_dma(const int8_t* __
               float4 sw = make_float4(sw0, sw0, sw0, sw0);
               if (w_per_row)
                 sw = *reinterpret_cast<const float4*>(scales + (wn * C::TN + j * 32 + g4 * 8 + (lane >> 5) * 4) * 4);
-              const float4 y = make_float4(((float)a[0] * sa) * sw.x, ((float)a[1] * sa) * sw.y,
-                                           ((float)a[2] * sa) * sw.z, ((float)a[3] * sa) * sw.w);
+              float4 y = make_float4(((float)a[0] * sa) * sw.x, ((float)a[1] * sa) * sw.y,
+                                     ((float)a[2] * sa) * sw.z, ((float)a[3] * sa) * sw.w);
+              if (ACT) {
+                y = make_float4(apply_act(y.x, epi.act), apply_act(y.y, epi.act), apply_act(y.z, epi.act),
+                                apply_act(y.w, epi.act));
+                amax = fmaxf(fmaxf(amax, fmaxf(fabsf(y.x), fabsf(y.y))), fmaxf(fabsf(y.z), fabsf(y.w)));
+              }
               if (Y) *reinterpret_cast<float4*>(Y + m * N + n) = y;
               if (SCORE && YREF) {
                 const float4 r = *reinterpret_cast<const float4*>(YREF + m * N + n);
@@ -675,7 +713,11 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void qgemm_dma(const int8_t* __
               if (n + e >= N) break;
               if (ACC) ACC[m * N + n + e] = a[e];
               if (want_y) {
-                const float y = ((float)a[e] * sa) * (w_per_row ? w_scale[n + e] : sw0);
+                float y = ((float)a[e] * sa) * (w_per_row ? w_scale[n + e] : sw0);
+                if (ACT) {
+                  y = apply_act(y, epi.act);
+                  amax = fmaxf(amax, fabsf(y));
+                }
                 if (Y) Y[m * N + n + e] = y;
                 if (SCORE && YREF) {
                   const float d = y - YREF[m * N + n + e];
@@ -705,24 +747,39 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void qgemm_dma(const int8_t* __
       PART[blockIdx.x] = t;
     }
   }
+  if (ACT && epi.amax) {  // one atomic per workgroup
+    const float w = wave_max(amax);
+    __syncthreads();
+    float* sm = reinterpret_cast<float*>(lds);
+    if (lane == 0) sm[wave] = w;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      float t = 0.0f;
+      for (int i = 0; i < C::NW; ++i) t = fmaxf(t, sm[i]);
+      atomicMax(epi.amax, abs_key(t));
+    }
+  }
 }
 
 template <int BM, int BN, int WM, int WN, int NSTAGE, bool W4, int KB = 128, int MINW = 1>
 static int launch_dma(const int8_t* a_q, const void* w_q, int64_t M, int64_t N, int64_t K,
                       const float* a_scale, const float* w_scale, int per_row, float* y_out,
-                      int32_t* acc_out, hipStream_t st, const float* y_ref = nullptr,
-                      double* partials = nullptr, int64_t* n_partials = nullptr) {
+                      int32_t* acc_out, hipStream_t st, EpiArgs epi = EpiArgs{nullptr, nullptr, 0, nullptr},
+                      int64_t* n_partials = nullptr) {
+  const float* y_ref = epi.yref;
   using C = DmaCfg<BM, BN, WM, WN, NSTAGE, W4, KB>;
   // float4 / int4 stores need every 4-group of n inside the row and 16-byte aligned
   const bool vec = (N & 3) == 0 && (!y_out || aligned16(y_out)) && (!acc_out || aligned16(acc_out)) &&
                    (!((y_out || y_ref) && per_row) || aligned16(w_scale)) && (!y_ref || aligned16(y_ref));
-  const bool score = y_ref != nullptr;
-  auto kern = score ? (vec ? qgemm_dma<BM, BN, WM, WN, NSTAGE, W4, true, KB, MINW, true>
-                           : qgemm_dma<BM, BN, WM, WN, NSTAGE, W4, false, KB, MINW, true>)
-                    : (vec ? qgemm_dma<BM, BN, WM, WN, NSTAGE, W4, true, KB, MINW, false>
-                           : qgemm_dma<BM, BN, WM, WN, NSTAGE, W4, false, KB, MINW, false>);
-  static bool attr_set[4] = {false, false, false, false};  // dynamic LDS above 64 KiB has to be allowed once per kernel
-  const int which = (score ? 2 : 0) + (vec ? 1 : 0);
+  const int mode = y_ref ? 1 : (epi.act || epi.amax) ? 2 : 0;
+  auto kern = mode == 1 ? (vec ? qgemm_dma<BM, BN, WM, WN, NSTAGE, W4, true, KB, MINW, 1>
+                               : qgemm_dma<BM, BN, WM, WN, NSTAGE, W4, false, KB, MINW, 1>)
+            : mode == 2 ? (vec ? qgemm_dma<BM, BN, WM, WN, NSTAGE, W4, true, KB, MINW, 2>
+                               : qgemm_dma<BM, BN, WM, WN, NSTAGE, W4, false, KB, MINW, 2>)
+                        : (vec ? qgemm_dma<BM, BN, WM, WN, NSTAGE, W4, true, KB, MINW, 0>
+                               : qgemm_dma<BM, BN, WM, WN, NSTAGE, W4, false, KB, MINW, 0>);
+  static bool attr_set[6] = {false, false, false, false, false, false};  // dynamic LDS above 64 KiB has to be allowed once per kernel
+  const int which = mode * 2 + (vec ? 1 : 0);
   if (!attr_set[which]) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
@@ -747,7 +804,7 @@ static int launch_dma(const int8_t* a_q, const void* w_q, int64_t M, int64_t N, 
   }
   const int remap = (grid % 8 == 0 && grid >= 16) ? 1 : 0;
   kern<<<(unsigned)grid, C::NT, C::LDS_BYTES, st>>>(a_q, w_q, M, N, K, a_scale, w_scale, per_row, y_out,
-                                                   acc_out, y_ref, partials, (int)tn, (int)tm, chunk, remap);
+                                                   acc_out, epi, (int)tn, (int)tm, chunk, remap);
   if (n_partials) *n_partials = grid;
   return launch_status();
 }
@@ -756,8 +813,8 @@ static int launch_dma(const int8_t* a_q, const void* w_q, int64_t M, int64_t N, 
 // leave one partial sum of (Y - y_ref)^2 per workgroup in `partials` and report how many.
 static int run_qgemm(const int8_t* a_q, const void* w_q, int w_storage_bits, int64_t M, int64_t N,
                      int64_t K, const float* a_scale, const float* w_scale, int w_gran, float* y_out,
-                     int32_t* acc_out, const float* y_ref, double* partials, int64_t* n_partials,
-                     hipStream_t st) {
+                     int32_t* acc_out, EpiArgs epi, int64_t* n_partials, hipStream_t st) {
+  const float* y_ref = epi.yref;
   if (!a_q || !w_q) return MPQ_ERR_NULL;
   if (!y_out && !acc_out && !y_ref) return MPQ_ERR_NULL;
   if ((y_out || y_ref) && (!a_scale || !w_scale)) return MPQ_ERR_NULL;
@@ -787,9 +844,9 @@ static int run_qgemm(const int8_t* a_q, const void* w_q, int w_storage_bits, int
     else if (N > 64 && tiles(128, 128) >= kNumCU / 2) pick = 128;
 #define MPQ_DMA(BM_, BN_, WM_, WN_, NS_)                                                              \
   (w4 ? launch_dma<BM_, BN_, WM_, WN_, NS_, true>(a_q, w_q, M, N, K, a_scale, w_scale, per_row, y_out, \
-                                                  acc_out, st, y_ref, partials, n_partials)           \
+                                                  acc_out, st, epi, n_partials)                        \
       : launch_dma<BM_, BN_, WM_, WN_, NS_, false>(a_q, w_q, M, N, K, a_scale, w_scale, per_row,     \
-                                                   y_out, acc_out, st, y_ref, partials, n_partials))
+                                                   y_out, acc_out, st, epi, n_partials))
     if (pick == 256) return MPQ_DMA(256, 256, 4, 2, 2);
     if (pick == 128)
       return (K >= 2048 || tiles(128, 128) <= kNumCU) ? MPQ_DMA(128, 128, 4, 2, 3) : MPQ_DMA(128, 128, 4, 2, 2);
@@ -797,8 +854,8 @@ static int run_qgemm(const int8_t* a_q, const void* w_q, int w_storage_bits, int
 #undef MPQ_DMA
   }
   const dim3 grid((unsigned)gx, (unsigned)gy);
-  if (w4) qgemm_k<true><<<grid, kGemmThreads, 0, st>>>(a_q, w_q, M, N, K, a_scale, w_scale, per_row, y_out, acc_out, y_ref, partials);
-  else qgemm_k<false><<<grid, kGemmThreads, 0, st>>>(a_q, w_q, M, N, K, a_scale, w_scale, per_row, y_out, acc_out, y_ref, partials);
+  if (w4) qgemm_k<true><<<grid, kGemmThreads, 0, st>>>(a_q, w_q, M, N, K, a_scale, w_scale, per_row, y_out, acc_out, epi);
+  else qgemm_k<false><<<grid, kGemmThreads, 0, st>>>(a_q, w_q, M, N, K, a_scale, w_scale, per_row, y_out, acc_out, epi);
   if (n_partials) *n_partials = gx * gy;
   return launch_status();
 }
@@ -819,8 +876,26 @@ extern "C" int mpq_qgemm(const int8_t* a_q, const void* w_q, int w_storage_bits,
   (void)ws;
   (void)ws_bytes;
   if (!y_out && !acc_out) return MPQ_ERR_NULL;
-  return run_qgemm(a_q, w_q, w_storage_bits, M, N, K, a_scale, w_scale, w_gran, y_out, acc_out, nullptr,
-                   nullptr, nullptr, (hipStream_t)stream);
+  return run_qgemm(a_q, w_q, w_storage_bits, M, N, K, a_scale, w_scale, w_gran, y_out, acc_out,
+                   EpiArgs{nullptr, nullptr, 0, nullptr}, nullptr, (hipStream_t)stream);
+}
+
+extern "C" int mpq_qgemm_act(const int8_t* a_q, const void* w_q, int w_storage_bits, int64_t M, int64_t N,
+                             int64_t K, const float* a_scale, const float* w_scale, int w_gran, int act,
+                             float* y_out, float* absmax_out, int accumulate, void* stream) {
+  if (!y_out) return MPQ_ERR_NULL;
+  if (act < MPQ_ACT_NONE || act > MPQ_ACT_GELU) return MPQ_ERR_SHAPE;
+  if (absmax_out && (reinterpret_cast<uintptr_t>(absmax_out) & 3u)) return MPQ_ERR_ALIGN;
+  hipStream_t st = (hipStream_t)stream;
+  unsigned* amax = reinterpret_cast<unsigned*>(absmax_out);
+  // validate before the fill: a failing call must leave the device untouched
+  if (!a_q || !w_q || !a_scale || !w_scale) return MPQ_ERR_NULL;
+  if (w_storage_bits != 8 && w_storage_bits != 4) return MPQ_ERR_BITS;
+  if (M <= 0 || N <= 0 || K <= 0 || K > 133143 || (w_storage_bits == 4 && (K & 1))) return MPQ_ERR_SHAPE;
+  if (w_gran != MPQ_PER_TENSOR && w_gran != MPQ_PER_ROW) return MPQ_ERR_GRAN;
+  if (amax && !accumulate) fill_u32_k<<<1, 1, 0, st>>>(amax, 0u);
+  return run_qgemm(a_q, w_q, w_storage_bits, M, N, K, a_scale, w_scale, w_gran, y_out, nullptr,
+                   EpiArgs{nullptr, nullptr, act, amax}, nullptr, st);
 }
 
 extern "C" size_t mpq_qgemm_score_workspace_bytes(int64_t M, int64_t N, int64_t K, int w_storage_bits) {
@@ -841,8 +916,8 @@ extern "C" int mpq_qgemm_score(const int8_t* a_q, const void* w_q, int w_storage
   hipStream_t st = (hipStream_t)stream;
   double* partials = reinterpret_cast<double*>(ws);
   int64_t count = 0;
-  const int rc = run_qgemm(a_q, w_q, w_storage_bits, M, N, K, a_scale, w_scale, w_gran, y_out, nullptr, y_ref,
-                           partials, &count, st);
+  const int rc = run_qgemm(a_q, w_q, w_storage_bits, M, N, K, a_scale, w_scale, w_gran, y_out, nullptr,
+                           EpiArgs{y_ref, partials, 0, nullptr}, &count, st);
   if (rc != MPQ_OK) return rc;
   sum_partials_k<<<1, kBlock, 0, st>>>(partials, count, sse_out);
   return launch_status();

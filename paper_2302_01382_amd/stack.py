@@ -3,11 +3,12 @@ the paper's searches (Alg. 1, Alg. 2) built from libmpq calls only.
 
 The model is y = W_L relu(... relu(W_1 x)): every layer's input is calibrated (max calibration,
 Sec. 3.1), quantized to `act_bits` (Eq. 1) and multiplied with the layer's weight codes at the
-width the configuration assigns to it (mpq_qgemm); the last layer takes the score against the fp32
-output of the unquantized model in its epilogue (mpq_qgemm_score).  The accuracy handed to the
+width the configuration assigns to it; ReLU and the calibration of the next layer's input happen in
+the GEMM's epilogue (mpq_qgemm_act), and the last layer takes the score against the fp32 output
+of the unquantized model in its epilogue (mpq_qgemm_score).  The accuracy handed to the
 searches is 1 - SSE / ||Y_ref||^2, a stand-in for the task accuracy the paper evaluates, which
-needs its datasets and trained weights.  torch supplies device memory, the ReLU between layers and
-the fp32 reference output, nothing else.
+needs its datasets and trained weights.  torch supplies device memory and the fp32 reference
+output, nothing else.
 """
 from __future__ import annotations
 
@@ -63,6 +64,10 @@ class QuantStack:
         self.a_codes = [torch.empty((M, w.shape[1]), dtype=torch.int8, device=dev) for w in self.weights]
         self.h = [torch.empty((M, w.shape[0]), dtype=f32, device=dev) for w in self.weights[:-1]]
         self.sse = torch.empty(1, dtype=torch.float64, device=dev)
+        # the model's input does not depend on the configuration: calibrated and quantized once
+        mpq.calibrate_absmax(self.x, out=self.a_absmax[0], ws=self.ws)
+        mpq.fake_quant(self.x, self.a_absmax[0], self.act_bits, want_y=False, codes=self.a_codes[0])
+        mpq.scale_from_absmax(self.a_absmax[0], self.act_bits, out=self.a_scale[0])
         self.evaluations = 0
         self.use_graphs = use_graphs
         self.graphs = {}
@@ -93,15 +98,15 @@ class QuantStack:
 
     def _layer(self, l: int, b: int):
         """Layer l at weight width b: input h_{l-1} (x for the first layer) -> h_l, or the score."""
-        torch, P = self.torch, mpq
-        h = self.x if l == 0 else self.h[l - 1]
-        P.calibrate_absmax(h, out=self.a_absmax[l], ws=self.ws)
-        P.fake_quant(h, self.a_absmax[l], self.act_bits, want_y=False, codes=self.a_codes[l])
-        P.scale_from_absmax(self.a_absmax[l], self.act_bits, out=self.a_scale[l])
+        P = mpq
+        if l > 0:   # the input's maximum came out of the previous layer's epilogue; x is quantized once, at set-up
+            P.fake_quant(self.h[l - 1], self.a_absmax[l], self.act_bits, want_y=False, codes=self.a_codes[l])
+            P.scale_from_absmax(self.a_absmax[l], self.act_bits, out=self.a_scale[l])
         wq, sw, store = self.w_q[l][b]
         if l + 1 < len(self.weights):
-            P.qgemm(self.a_codes[l], wq, self.a_scale[l], sw, store, self.w_gran, y=self.h[l], ws=self.ws)
-            torch.relu_(self.h[l])
+            # ReLU and the max calibration of the next layer's input are taken in the epilogue
+            P.qgemm_act(self.a_codes[l], wq, self.a_scale[l], sw, P.ACT_RELU, store, self.w_gran, y=self.h[l],
+                        absmax=self.a_absmax[l + 1])
         else:
             P.qgemm_score(self.a_codes[l], wq, self.a_scale[l], sw, self.y_ref, store, self.w_gran,
                           out=self.sse, ws=self.ws)

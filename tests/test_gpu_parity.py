@@ -359,6 +359,39 @@ def test_qgemm_score_every_tile_size(mnk, wbits):
     assert host(sse_m)[0] == pytest.approx(want, rel=RTOL_SSE)
 
 
+# ------------------------------------------------------------------- qgemm + activation + absmax
+@pytest.mark.parametrize("mnk,wbits", [((64, 256, 256), 8), ((33, 31, 130), 8), ((300, 70, 48), 4), ((2048, 2048, 384), 8),
+                                        ((4100, 4092, 160), 4), ((2085, 2046, 112), 8), ((6272, 256, 512), 4)])
+@pytest.mark.parametrize("act", [1, 2])
+def test_qgemm_act_matches_the_composition(mnk, wbits, act):
+    M, N, K = mnk
+    q = 127 if wbits == 8 else 7
+    a, w = rand_codes((M, K), 127, 60), rand_codes((N, K), q, 61)
+    ws = w if wbits == 8 else oracle.pack4(w)
+    r = np.random.Generator(np.random.PCG64(62))
+    sa = np.array([0.002], np.float32)
+    sw = (r.random(N).astype(np.float32) + 0.5) * np.float32(1e-3)   # outputs of a few units: both GELU tails occur
+    y_o, am_o = oracle.qgemm_act(a, ws, sa, sw, act, wbits, oracle.PER_ROW)
+    for mk in (dev, dev_misaligned):
+        y, am = mpq.qgemm_act(mk(a), mk(ws), dev(sa), dev(sw), act, wbits, mpq.PER_ROW)
+        y_h = host(y)
+        if act == 1:   # ReLU of a value that agrees to 1e-5 relative
+            np.testing.assert_allclose(y_h, y_o, rtol=RTOL_Y, atol=0)
+        else:          # GELU with the fp32 erf: relative, except in the negative tail where 1 + erf cancels
+            pre, _ = oracle.qgemm(a, ws, sa, sw, wbits, oracle.PER_ROW)
+            assert (np.abs(y_h - y_o) <= 2e-5 * np.abs(y_o) + 2e-7 * np.abs(pre)).all()
+        # the absmax is exact for the values the kernel itself wrote, and within tolerance of the oracle's
+        assert host(am)[0] == np.abs(y_h).max()
+        assert host(am)[0] == pytest.approx(am_o[0], rel=2e-5)
+    # running maximum over two calls
+    am = dev(np.array([1e30], np.float32))
+    mpq.qgemm_act(dev(a), dev(ws), dev(sa), dev(sw), act, wbits, mpq.PER_ROW, absmax=am, accumulate=True)
+    assert host(am)[0] == np.float32(1e30)
+    y, none = mpq.qgemm_act(dev(a), dev(ws), dev(sa), dev(sw), act, wbits, mpq.PER_ROW, want_absmax=False)
+    assert none is None
+    np.testing.assert_array_equal(host(y), y_h if False else host(mpq.qgemm_act(dev(a), dev(ws), dev(sa), dev(sw), act, wbits, mpq.PER_ROW)[0]))
+
+
 # ---------------------------------------------------------------------------------- sse pair
 @pytest.mark.parametrize("n", [1, 7, 4096, 100003, 1 << 20])
 def test_sse_pair(n):

@@ -417,3 +417,14 @@ def test_sse_pair_against_numpy():
     want = math.fsum(((a.astype(np.float64) - b.astype(np.float64)) ** 2).tolist())
     assert oracle.sse_pair(a, b) == pytest.approx(want, rel=1e-12)
     assert oracle.sse_pair(a, a) == 0.0
+
+
+# ------------------------------------------------------------------------------- activations
+def test_oracle_gelu_is_x_times_the_gaussian_distribution_function():
+    """Pin of the oracle's activation against scipy's normal CDF (a different routine than erfc)."""
+    from scipy.stats import norm
+    x = np.linspace(-9, 9, 2001).astype(np.float32)
+    want = (x.astype(np.float64) * norm.cdf(x.astype(np.float64))).astype(np.float32)
+    np.testing.assert_array_equal(oracle.activation(x, oracle.ACT_GELU), want)
+    np.testing.assert_array_equal(oracle.activation(x, oracle.ACT_RELU), np.maximum(x, 0))
+    np.testing.assert_array_equal(oracle.activation(x, oracle.ACT_NONE), x)
