@@ -156,6 +156,13 @@ def test_config5_candidate_scoring_chain():
                                    oracle.scale_from_absmax(am_w1_o, bw1), st1)
         np.testing.assert_array_equal(host(acc1)[rows], acc1_o)
         np.testing.assert_allclose(host(h)[rows], h_o, rtol=RTOL_Y, atol=0)
+        # the fused form of the same stage: GELU and the calibration of its output in the epilogue
+        hf, am_f = mpq.qgemm_act(cx, cw1, mpq.scale_from_absmax(am_x, ba1), mpq.scale_from_absmax(am_w1, bw1),
+                                 mpq.ACT_GELU, st1)
+        hf_h = host(hf)
+        gelu_o = oracle.activation(h_o, oracle.ACT_GELU)
+        assert (np.abs(hf_h[rows] - gelu_o) <= 2e-5 * np.abs(gelu_o) + 2e-7 * np.abs(h_o)).all()
+        assert host(am_f)[0] == np.abs(hf_h).max()
         g = t.nn.functional.gelu(h)  # not a libmpq call: the same tensor goes to both sides
         g_h = host(g)
         am_g = mpq.calibrate_absmax(g)
@@ -174,6 +181,10 @@ def test_config5_candidate_scoring_chain():
         sse = host(mpq.sse_pair(y, y_ref))[0]
         want = oracle.sse_pair(y_h, y_ref_h)
         assert sse == pytest.approx(want, rel=RTOL_SSE)
+        # the same score taken in the second GEMM's epilogue, Y never written
+        fused, _ = mpq.qgemm_score(cg, cw2, mpq.scale_from_absmax(am_g, ba2), mpq.scale_from_absmax(am_w2, bw2),
+                                   y_ref, st2)
+        assert host(fused)[0] == pytest.approx(want, rel=RTOL_SSE)
         mse_gpu.append(sse / y_h.size)
         mse_host.append(want / y_h.size)
     # the best candidate is the same on both sides when the oracle's margin allows a decision
