@@ -835,12 +835,17 @@ static int run_qgemm(const int8_t* a_q, const void* w_q, int w_storage_bits, int
   const bool fast = aligned16(a_q) && aligned16(w_q) && (K % (w4 ? 32 : 16)) == 0 && M < (1ll << 31) && N < (1ll << 31);
   if (fast) {
     // tile choice (from sweeps over the configured shapes): 256 x 256 when that gives at least
-    // three CUs in four a tile, 128 x 128 when it gives at least half of them one, else 64 x 64.
+    // three CUs in four a tile; else 192 x 192 (six waves) when it covers the problem in exactly
+    // one round with at least three CUs in four busy and next to no padding (the BERT-base
+    // widths: 768 = 4 x 192 gives 12288 x 768 exactly 256 tiles where 256 x 256 gives 144);
+    // else 128 x 128 when it gives at least half of the CUs a tile, else 64 x 64.
     // 128 x 128 runs three stages (one workgroup per CU) when there is at most one tile per CU
     // anyway or k is long, two stages (two workgroups per CU) otherwise.
     auto tiles = [&](int64_t bm, int64_t bn) { return ((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
     int pick = 64;
+    const int64_t t192 = tiles(192, 192);
     if (N > 128 && tiles(256, 256) >= kNumCU * 3 / 4) pick = 256;
+    else if (N % 192 == 0 && t192 <= kNumCU && t192 >= kNumCU * 3 / 4 && t192 * 192 * 192 <= M * N + M * N / 32) pick = 192;
     else if (N > 64 && tiles(128, 128) >= kNumCU / 2) pick = 128;
 #define MPQ_DMA(BM_, BN_, WM_, WN_, NS_)                                                              \
   (w4 ? launch_dma<BM_, BN_, WM_, WN_, NS_, true>(a_q, w_q, M, N, K, a_scale, w_scale, per_row, y_out, \
@@ -848,6 +853,7 @@ static int run_qgemm(const int8_t* a_q, const void* w_q, int w_storage_bits, int
       : launch_dma<BM_, BN_, WM_, WN_, NS_, false>(a_q, w_q, M, N, K, a_scale, w_scale, per_row,     \
                                                    y_out, acc_out, st, epi, n_partials))
     if (pick == 256) return MPQ_DMA(256, 256, 4, 2, 2);
+    if (pick == 192) return K >= 1024 ? MPQ_DMA(192, 192, 3, 2, 3) : MPQ_DMA(192, 192, 3, 2, 2);
     if (pick == 128)
       return (K >= 2048 || tiles(128, 128) <= kNumCU) ? MPQ_DMA(128, 128, 4, 2, 3) : MPQ_DMA(128, 128, 4, 2, 2);
     return MPQ_DMA(64, 64, 2, 2, 3);

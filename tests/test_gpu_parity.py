@@ -265,9 +265,10 @@ def test_qgemm_packed_int4_weights_bit_exact(mnk):
 
 @pytest.mark.parametrize("mnk,wbits", [((4096, 4096, 256), 8), ((4100, 4092, 160), 4), ((2048, 2048, 384), 8),
                                         ((2085, 2047, 96), 4), ((2085, 2046, 112), 8), ((16384, 1024, 4096), 8),
-                                        ((1568, 2048, 2048), 4), ((1568, 512, 4608), 8), ((300, 200, 1152), 4)])
+                                        ((1568, 2048, 2048), 4), ((1568, 512, 4608), 8), ((300, 200, 1152), 4),
+                                        ((12288, 768, 256), 8), ((12288, 768, 1152), 4), ((12280, 768, 160), 8)])
 def test_qgemm_large_tiles_on_sampled_rows(mnk, wbits):
-    """Shapes that select the 128 x 128 and 256 x 256 tiles (ragged edges, N not a multiple of 4);
+    """Shapes that select the 128 x 128, 192 x 192 and 256 x 256 tiles (ragged edges, N not a multiple of 4);
     rows of the product are independent, so the oracle checks a sample of rows exactly."""
     M, N, K = mnk
     q = 127 if wbits == 8 else 7
@@ -338,7 +339,8 @@ def test_qgemm_score_small_shapes(mnk, wbits):
 
 
 @pytest.mark.parametrize("mnk,wbits", [((2048, 2048, 384), 8), ((4100, 4092, 160), 4), ((2085, 2046, 112), 8),
-                                        ((300, 200, 1152), 4), ((1568, 512, 1024), 8), ((6272, 256, 512), 4)])
+                                        ((300, 200, 1152), 4), ((1568, 512, 1024), 8), ((6272, 256, 512), 4),
+                                        ((12288, 768, 128), 8)])
 def test_qgemm_score_every_tile_size(mnk, wbits):
     """Shapes that select the 64, 128 and 256 tiles, with ragged edges, N not a multiple of 4 and
     several tiles per workgroup; the whole product is small enough for the oracle."""
@@ -361,7 +363,8 @@ def test_qgemm_score_every_tile_size(mnk, wbits):
 
 # ------------------------------------------------------------------- qgemm + activation + absmax
 @pytest.mark.parametrize("mnk,wbits", [((64, 256, 256), 8), ((33, 31, 130), 8), ((300, 70, 48), 4), ((2048, 2048, 384), 8),
-                                        ((4100, 4092, 160), 4), ((2085, 2046, 112), 8), ((6272, 256, 512), 4)])
+                                        ((4100, 4092, 160), 4), ((2085, 2046, 112), 8), ((6272, 256, 512), 4),
+                                        ((12288, 768, 128), 4)])
 @pytest.mark.parametrize("act", [1, 2])
 def test_qgemm_act_matches_the_composition(mnk, wbits, act):
     M, N, K = mnk
