@@ -17,7 +17,10 @@ Other workloads (the parity-test configurations, measured with the same machiner
           (cfg4-unfused: one call per granularity and per noise level)
     cfg5  64 candidate bit configurations of a BERT-large FFN block at M = 16384, back to back;
           GELU and the calibration of its output in the first GEMM's epilogue, the output score in
-          the second's (cfg5-unfused: mpq_qgemm, torch GELU, mpq_calibrate_absmax, mpq_sse_pair)
+          the second's
+          (cfg5-twopass: the first GEMM runs twice, absmax of GELU(H) only, then its int8 codes
+           straight from the epilogue, no fp32 H in HBM;
+           cfg5-unfused: mpq_qgemm, torch GELU, mpq_calibrate_absmax, mpq_sse_pair)
     search  Alg. 1 / Alg. 2 over a 24-layer stack, evaluations per second
     latency qgemm latency table at batch 1 and the mixed-precision latency estimate built from it
 All inputs are resident in HBM before the timed region.  Prints ONE JSON line.
@@ -368,7 +371,8 @@ def workload_cfg4(torch, P, workloads, fused):
 
 # ------------------------------------------------------------------------------------------------
 # configuration 5: candidate scoring on a BERT-large FFN block
-def workload_cfg5(torch, P, workloads, fused):
+def workload_cfg5(torch, P, workloads, mode):
+    fused = mode != "unfused"
     x, w1, w2 = workloads.cfg5_tensors()
     cands = workloads.cfg5_candidates()
     dx, dw1, dw2 = torch.from_numpy(x).cuda(), torch.from_numpy(w1).cuda(), torch.from_numpy(w2).cuda()
@@ -418,7 +422,14 @@ def workload_cfg5(torch, P, workloads, fused):
             q2, st2 = quant_w(rec, dw2, am_w2, bw2, cw2, pw2)
             with rec("fake_quant", 5 * dx.numel()):
                 P.fake_quant(dx, am_x, ba1, want_y=False, codes=cx)
-            if fused:  # GELU and the calibration of its output happen in the first GEMM's epilogue
+            if mode == "twopass":
+                # The first GEMM runs twice and stores no fp32 output: pass one keeps only the absmax
+                # of GELU(H), pass two quantizes GELU(H) with it in the epilogue and stores int8 codes.
+                with rec("qgemm", M * K1 + N1 * K1 * st1 // 8, 2 * M * N1 * K1):
+                    P.qgemm_act(cx, q1, s_x[ba1], s_w1[bw1], P.ACT_GELU, st1, want_y=False, absmax=am_h)
+                with rec("qgemm", M * K1 + N1 * K1 * st1 // 8 + M * N1, 2 * M * N1 * K1):
+                    P.qgemm_act_codes(cx, q1, s_x[ba1], s_w1[bw1], P.ACT_GELU, am_h, ba2, st1, codes=ch)
+            elif fused:  # GELU and the calibration of its output happen in the first GEMM's epilogue
                 with rec("qgemm", M * K1 + N1 * K1 * st1 // 8 + 4 * M * N1, 2 * M * N1 * K1):
                     P.qgemm_act(cx, q1, s_x[ba1], s_w1[bw1], P.ACT_GELU, st1, y=h, absmax=am_h)
             else:
@@ -427,8 +438,9 @@ def workload_cfg5(torch, P, workloads, fused):
                 torch.ops.aten.gelu_(h)  # torch, in place, same stream
                 with rec("absmax", 4 * h.numel()):
                     P.calibrate_absmax(h, out=am_h, ws=ws)
-            with rec("fake_quant", 5 * h.numel()):
-                P.fake_quant(h, am_h, ba2, want_y=False, codes=ch)
+            if mode != "twopass":
+                with rec("fake_quant", 5 * h.numel()):
+                    P.fake_quant(h, am_h, ba2, want_y=False, codes=ch)
             P.scale_from_absmax(am_h, ba2, out=s_h)
             if fused:  # the score is taken in the epilogue: Y_ref is read, Y is never written
                 with rec("qgemm", M * N1 + N2 * N1 * st2 // 8 + 4 * M * N2, 2 * M * N2 * N1):
@@ -442,15 +454,20 @@ def workload_cfg5(torch, P, workloads, fused):
     def snapshot():
         return [scores.clone()]
 
-    per_cand = (4.75 * (dw1.numel() + dw2.numel()) + 5 * dx.numel() + (M * K1 + N1 * K1 + 4 * M * N1)
-                + (0 if fused else 4 * M * N1) + 5 * M * N1 + (M * N1 + N2 * N1 + 4 * M * N2)
+    if mode == "twopass":
+        first = 2 * (M * K1 + N1 * K1) + M * N1
+    else:
+        first = (M * K1 + N1 * K1 + 4 * M * N1) + (0 if fused else 4 * M * N1) + 5 * M * N1
+    per_cand = (4.75 * (dw1.numel() + dw2.numel()) + 5 * dx.numel() + first + (M * N1 + N2 * N1 + 4 * M * N2)
                 + (0 if fused else 8 * M * N2))
     nbytes = int(len(cands) * per_cand + 4 * (dx.numel() + dw1.numel() + dw2.numel()))
-    ops = len(cands) * (2 * M * N1 * K1 + 2 * M * N2 * N1)
+    ops = len(cands) * ((2 if mode == "twopass" else 1) * 2 * M * N1 * K1 + 2 * M * N2 * N1)
     label = ("cfg5: 64 candidate bit configurations of a BERT-large FFN block (1024 -> 4096 -> 1024) at "
              "M = 16384, back to back: re-quantize, qgemm, GELU, calibrate, re-quantize, qgemm, output SSE"
-             + ("; GELU + calibration in the first GEMM's epilogue, the score in the second's" if fused
-                else "; GELU by torch, calibration and score as passes of their own"))
+             + {"twopass": "; the first GEMM runs twice (absmax of GELU(H), then int8 codes of GELU(H) from the "
+                           "epilogue: no fp32 H in HBM), the score in the second GEMM's epilogue",
+                "onepass": "; GELU + calibration in the first GEMM's epilogue, the score in the second's",
+                "unfused": "; GELU by torch, calibration and score as passes of their own"}[mode])
     return step, snapshot, nbytes, ops, label, len(cands)
 
 
@@ -582,8 +599,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", choices=["cfg2", "cfg3", "cfg4", "cfg4-unfused", "cfg5", "cfg5-unfused", "search", "latency"], default="cfg2")
-    ap.add_argument("--cpu-sample-rows", type=int, default=1024)
+    ap.add_argument("--workload", choices=["cfg2", "cfg3", "cfg4", "cfg4-unfused", "cfg5", "cfg5-twopass", "cfg5-unfused", "search", "latency"], default="cfg2")
+    ap.add_argument("--cpu-sample-rows", type=int, default=2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain device copy of known size (225792 KiB) three times before the "
@@ -618,7 +635,7 @@ def main():
     elif args.workload in ("cfg4", "cfg4-unfused"):
         step, snapshot, nbytes, ops, label = workload_cfg4(torch, mpq, workloads, args.workload == "cfg4")
     else:
-        step, snapshot, nbytes, ops, label, ncand = workload_cfg5(torch, mpq, workloads, args.workload == "cfg5")
+        step, snapshot, nbytes, ops, label, ncand = workload_cfg5(torch, mpq, workloads, {"cfg5": "onepass", "cfg5-twopass": "twopass", "cfg5-unfused": "unfused"}[args.workload])
         extra["candidates_per_step"] = ncand
         args.steps = min(args.steps, 5)   # one step is 64 candidates (~20 ms); keep the GPU time bounded
     torch.cuda.synchronize()

@@ -144,18 +144,33 @@ int mpq_sse_pair(const float* y, const float* y_ref, int64_t n, double* sse_out,
 
 /* ---- the layer of mpq_qgemm with what follows it in "Evaluate f(x, w)" taken in its epilogue ----
  * y_out = act(Y) with Y as mpq_qgemm defines it, act one of mpq_act:
- *   MPQ_ACT_RELU  max(Y, 0);   MPQ_ACT_GELU  Y * Phi(Y), evaluated as Y/2 * (1 + erf(Y / sqrt 2))
- *   in fp32: within 1e-5 relative of the exact value, or 2e-7 |Y| where that is larger (the
- *   negative tail, where GELU is below 1e-4 |Y|).
+ *   MPQ_ACT_RELU  max(Y, 0);   MPQ_ACT_GELU  Y * Phi(Y), Phi the standard normal distribution
+ *   function, evaluated in fp32 from a fitted approximation of its tail: within 1e-5 relative of
+ *   the exact value, or 4e-7 |Y| where that is larger (beyond Y = -6, where GELU is below 1e-9 |Y|).
  * absmax_out nullable float[1]: max |y_out|, i.e. the max calibration (Sec. 3.1) of the next
  *   layer's input, taken on the values while they are in registers.  accumulate = 0 overwrites
  *   it, 1 keeps a running maximum (absmax_out must then hold a valid non-negative value).
- *   The maximum is exact (order independent).  y_out is required; other arguments and errors as
- *   mpq_qgemm, plus MPQ_ERR_SHAPE for an unknown act.  No workspace. */
+ *   The maximum is exact (order independent).
+ * y_out      nullable when absmax_out is given: the calibration-only pass, which computes the
+ *   product and keeps nothing but the maximum (no fp32 output travels to HBM).
+ * Other arguments and errors as mpq_qgemm, plus MPQ_ERR_SHAPE for an unknown act.  No workspace. */
 enum mpq_act { MPQ_ACT_NONE = 0, MPQ_ACT_RELU = 1, MPQ_ACT_GELU = 2 };
 int mpq_qgemm_act(const int8_t* a_q, const void* w_q, int w_storage_bits, int64_t M, int64_t N,
                   int64_t K, const float* a_scale, const float* w_scale, int w_gran, int act,
                   float* y_out, float* absmax_out, int accumulate, void* stream);
+
+/* ---- the same layer with Eq. 1 applied to its activated output in the epilogue ----------------
+ * codes_out[m][n] = clamp(RNE(act(Y)[m][n] * inv_b), +-qmax_b) as int8 [M x N], inv_b = qmax_b /
+ * absmax[0]: exactly the codes mpq_fake_quant(per tensor, bits) gives for the y_out of
+ * mpq_qgemm_act, without that fp32 tensor ever being stored.  Meant as the second of two passes
+ * over the product: mpq_qgemm_act(y_out = NULL) finds absmax, this call quantizes with it, and
+ * the next layer's GEMM reads codes_out (its activation step is mpq_scale_from_absmax(absmax, bits)).
+ * Recomputing the int8 product costs less than writing and re-reading 4 bytes per output.
+ * absmax     device float[1], required (any non-negative value; 0 gives all-zero codes).
+ * bits       2..8.  codes_out required.  Other arguments and errors as mpq_qgemm_act. */
+int mpq_qgemm_act_codes(const int8_t* a_q, const void* w_q, int w_storage_bits, int64_t M, int64_t N,
+                        int64_t K, const float* a_scale, const float* w_scale, int w_gran, int act,
+                        const float* absmax, int bits, int8_t* codes_out, void* stream);
 
 /* ---- "Evaluate f(x, w) and save accuracy a" of Alg. 1 / Alg. 2 in one call -------------------
  * The layer of mpq_qgemm with the score of mpq_sse_pair taken in its epilogue:

@@ -26,21 +26,47 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 //  - score: accumulate sum (Y - yref)^2, one double partial per workgroup in `part`;
 //  - activation: Y <- act(Y) before it is stored (1 = ReLU, 2 = GELU), and the largest |Y| after
 //    the activation merged into amax[0] (an integer atomic max over the bit patterns of the
-//    non-negative floats: exact and independent of the order).
+//    non-negative floats: exact and independent of the order);
+//  - codes: the activated output quantized on the spot (Eq. 1 with the absmax in q_absmax[0], which
+//    an earlier pass over the same product found) and stored as int8 codes, so that the fp32 layer
+//    output never travels to HBM and back on its way into the next layer's GEMM.
 struct EpiArgs {
   const float* yref;
   double* part;
   int act;
   unsigned* amax;
+  const float* q_absmax;
+  int q_bits;
+  int8_t* codes;
 };
+constexpr EpiArgs kNoEpi = {nullptr, nullptr, 0, nullptr, nullptr, 0, nullptr};
 
-// GELU(x) = x Phi(x) = x/2 * (1 + erf(x / sqrt 2)).  The sum cancels in the negative tail, so the
-// error there is absolute, about 1e-7 |x| (GELU itself is below 1e-4 |x| beyond x = -3.7); the
-// erfc form would be accurate to the last bit there too, but costs three times the arithmetic, and
-// the epilogue's arithmetic is not hidden behind anything.
+// GELU(y) = y Phi(y).  The epilogue's arithmetic is not hidden behind anything (every wave of the
+// workgroup is in its epilogue at the same time), so Phi is evaluated in about twenty lane
+// operations instead of the library erf's fifty: with t = |y|,
+//   Phi(-t) = 1/2 erfc(t / sqrt 2) = exp(-t^2 / 2) P(u),  u = 1 / (1 + 0.28 t),
+// P a degree-6 polynomial fitted (minimax in the relative error, 4e-7 on 0 <= t <= 6) to
+// 1/2 erfcx(t / sqrt 2), and Phi(t) = 1 - Phi(-t).  The form keeps the RELATIVE accuracy in the
+// negative tail, where 1 + erf would cancel: in fp32 the result is within 2e-6 relative of the
+// exact GELU for y >= -6 (the rounding of t^2 in the exponent dominates) and within 4e-7 |y|
+// absolute everywhere (beyond y = -6 GELU itself is below 1e-9 |y|).
+__device__ __forceinline__ float gelu_f(float y) {
+  const float t = fabsf(y);
+  const float u = __builtin_amdgcn_rcpf(__builtin_fmaf(t, 0.28f, 1.0f));
+  float p = -0.11208509653806686f;
+  p = __builtin_fmaf(p, u, 0.41932520270347595f);
+  p = __builtin_fmaf(p, u, -0.29365190863609314f);
+  p = __builtin_fmaf(p, u, 0.32605481147766113f);
+  p = __builtin_fmaf(p, u, 0.035669293254613876f);
+  p = __builtin_fmaf(p, u, 0.12578752636909485f);
+  p = __builtin_fmaf(p, u, -0.0010996352648362517f);
+  const float tail = __builtin_amdgcn_exp2f((t * t) * -0.72134752044448170f) * p;  // exp(-t^2/2) P(u)
+  return y * (y < 0.0f ? tail : 1.0f - tail);
+}
+
 __device__ __forceinline__ float apply_act(float y, int act) {
   if (act == 1) return fmaxf(y, 0.0f);
-  if (act == 2) return (0.5f * y) * (1.0f + erff(y * 0.70710678118654752f));
+  if (act == 2) return gelu_f(y);
   return y;
 }
 
@@ -194,10 +220,15 @@ __global__ __launch_bounds__(kGemmThreads) void qgemm_k(const int8_t* __restrict
   }
 
   // epilogue: lane holds column l%32 and rows 8*(v/4) + 4*(l/32) + v%4 of each 32x32 tile
-  const bool want_y = Y || YREF;
+  const bool want_y = Y || YREF || epi.amax || epi.codes;
   const float sa = want_y ? a_scale[0] : 0.0f;
   float sse = 0.0f;  // this lane's share of sum (Y - YREF)^2
   float amax = 0.0f;
+  float q_scale = 0.0f, q_inv = 0.0f, q_max = 0.0f;
+  if (epi.codes) {
+    bit_constants(epi.q_absmax[0], epi.q_bits, q_scale, q_inv);
+    q_max = (float)((1 << (epi.q_bits - 1)) - 1);
+  }
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
     const int64_t n = n0 + wn * 64 + j * 32 + (lane & 31);
@@ -215,6 +246,7 @@ __global__ __launch_bounds__(kGemmThreads) void qgemm_k(const int8_t* __restrict
         const float y = apply_act(((float)a * sa) * sw, epi.act);
         amax = fmaxf(amax, fabsf(y));
         if (Y) Y[m * N + n] = y;
+        if (epi.codes) epi.codes[m * N + n] = (int8_t)(int)code_f(y, q_inv, q_max);
         if (YREF) {
           const float d = y - YREF[m * N + n];
           sse = __builtin_fmaf(d, d, sse);
@@ -535,8 +567,9 @@ __device__ __forceinline__ void k_substep(v16i (&acc)[C::FM][C::FN], const v4i (
 // that a tile always starts in stage 0.)  Chunks stay short so that the hardware dispatcher, not a
 // fixed assignment, balances the load when other kernels hold some of the CUs.
 // MINW: waves the register allocation must leave room for on one SIMD.
-// EPI: 0 plain, 1 score, 2 activation and absmax of the output (see EpiArgs); variants of their
-// own because the largest tile has no registers to spare for them in the plain kernel.
+// EPI: 0 plain, 1 score, 2 activation and absmax of the output, 3 activation and int8 codes of the
+// output (see EpiArgs); variants of their own because the largest tile has no registers to spare
+// for them in the plain kernel.
 template <int BM, int BN, int WM, int WN, int NSTAGE, bool W4, bool VEC, int KB, int MINW, int EPI>
 __global__ __launch_bounds__(WM * WN * 64, MINW) void qgemm_dma(const int8_t* __restrict__ A,
                                                           const void* __restrict__ Wv, int64_t M,
@@ -547,7 +580,8 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void qgemm_dma(const int8_t* __
                                                           int32_t* __restrict__ ACC, EpiArgs epi,
                                                           int tiles_n, int tiles_m, int chunk,
                                                           int remap) {
-  constexpr bool SCORE = EPI == 1, ACT = EPI == 2;
+  constexpr bool SCORE = EPI == 1, ACT = EPI >= 2, AMAX = EPI == 2, QOUT = EPI == 3;
+  int8_t* __restrict__ CODES = epi.codes;
   const float* __restrict__ YREF = epi.yref;
   double* __restrict__ PART = epi.part;
   using C = DmaCfg<BM, BN, WM, WN, NSTAGE, W4, KB>;
@@ -576,7 +610,13 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void qgemm_dma(const int8_t* __
   // Per-channel W scales of an output tile travel through LDS (one wave-load of 256 floats, issued
   // by every wave ahead of the tile's first k tile, into the buffer `par` selects): the epilogue
   // then needs no global loads between its stores and no registers to park the scales in.
-  const bool want_y = Y || (SCORE && YREF);
+  const bool want_y = Y || (SCORE && YREF) || (AMAX && epi.amax) || (QOUT && CODES);
+  float q_inv = 0.0f, q_max = 0.0f;
+  if (QOUT) {
+    float q_scale;
+    bit_constants(epi.q_absmax[0], epi.q_bits, q_scale, q_inv);
+    q_max = (float)((1 << (epi.q_bits - 1)) - 1);
+  }
   const bool lds_scales = VEC && want_y && w_per_row;
   unsigned par = 0;
   auto issue_scales = [&](int64_t n_first, unsigned which) {
@@ -692,9 +732,16 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void qgemm_dma(const int8_t* __
               if (ACT) {
                 y = make_float4(apply_act(y.x, epi.act), apply_act(y.y, epi.act), apply_act(y.z, epi.act),
                                 apply_act(y.w, epi.act));
-                amax = fmaxf(fmaxf(amax, fmaxf(fabsf(y.x), fabsf(y.y))), fmaxf(fabsf(y.z), fabsf(y.w)));
+                if (AMAX) amax = fmaxf(fmaxf(amax, fmaxf(fabsf(y.x), fabsf(y.y))), fmaxf(fabsf(y.z), fabsf(y.w)));
               }
               if (Y) *reinterpret_cast<float4*>(Y + m * N + n) = y;
+              if (QOUT && CODES) {  // four codes, lowest n in the lowest byte
+                const unsigned c0 = (unsigned)(int)code_f(y.x, q_inv, q_max) & 0xFFu;
+                const unsigned c1 = (unsigned)(int)code_f(y.y, q_inv, q_max) & 0xFFu;
+                const unsigned c2 = (unsigned)(int)code_f(y.z, q_inv, q_max) & 0xFFu;
+                const unsigned c3 = (unsigned)(int)code_f(y.w, q_inv, q_max);
+                *reinterpret_cast<unsigned*>(CODES + m * N + n) = c0 | (c1 << 8) | (c2 << 16) | (c3 << 24);
+              }
               if (SCORE && YREF) {
                 const float4 r = *reinterpret_cast<const float4*>(YREF + m * N + n);
                 float d = y.x - r.x;
@@ -716,9 +763,10 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void qgemm_dma(const int8_t* __
                 float y = ((float)a[e] * sa) * (w_per_row ? w_scale[n + e] : sw0);
                 if (ACT) {
                   y = apply_act(y, epi.act);
-                  amax = fmaxf(amax, fabsf(y));
+                  if (AMAX) amax = fmaxf(amax, fabsf(y));
                 }
                 if (Y) Y[m * N + n + e] = y;
+                if (QOUT && CODES) CODES[m * N + n + e] = (int8_t)(int)code_f(y, q_inv, q_max);
                 if (SCORE && YREF) {
                   const float d = y - YREF[m * N + n + e];
                   sse = __builtin_fmaf(d, d, sse);
@@ -747,7 +795,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void qgemm_dma(const int8_t* __
       PART[blockIdx.x] = t;
     }
   }
-  if (ACT && epi.amax) {  // one atomic per workgroup
+  if (AMAX && epi.amax) {  // one atomic per workgroup
     const float w = wave_max(amax);
     __syncthreads();
     float* sm = reinterpret_cast<float*>(lds);
@@ -764,21 +812,24 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void qgemm_dma(const int8_t* __
 template <int BM, int BN, int WM, int WN, int NSTAGE, bool W4, int KB = 128, int MINW = 1>
 static int launch_dma(const int8_t* a_q, const void* w_q, int64_t M, int64_t N, int64_t K,
                       const float* a_scale, const float* w_scale, int per_row, float* y_out,
-                      int32_t* acc_out, hipStream_t st, EpiArgs epi = EpiArgs{nullptr, nullptr, 0, nullptr},
+                      int32_t* acc_out, hipStream_t st, EpiArgs epi = kNoEpi,
                       int64_t* n_partials = nullptr) {
   const float* y_ref = epi.yref;
   using C = DmaCfg<BM, BN, WM, WN, NSTAGE, W4, KB>;
   // float4 / int4 stores need every 4-group of n inside the row and 16-byte aligned
   const bool vec = (N & 3) == 0 && (!y_out || aligned16(y_out)) && (!acc_out || aligned16(acc_out)) &&
-                   (!((y_out || y_ref) && per_row) || aligned16(w_scale)) && (!y_ref || aligned16(y_ref));
-  const int mode = y_ref ? 1 : (epi.act || epi.amax) ? 2 : 0;
+                   (!((y_out || y_ref || epi.amax || epi.codes) && per_row) || aligned16(w_scale)) &&
+                   (!y_ref || aligned16(y_ref)) && (!epi.codes || (reinterpret_cast<uintptr_t>(epi.codes) & 3u) == 0);
+  const int mode = y_ref ? 1 : epi.codes ? 3 : (epi.act || epi.amax) ? 2 : 0;
   auto kern = mode == 1 ? (vec ? qgemm_dma<BM, BN, WM, WN, NSTAGE, W4, true, KB, MINW, 1>
                                : qgemm_dma<BM, BN, WM, WN, NSTAGE, W4, false, KB, MINW, 1>)
             : mode == 2 ? (vec ? qgemm_dma<BM, BN, WM, WN, NSTAGE, W4, true, KB, MINW, 2>
                                : qgemm_dma<BM, BN, WM, WN, NSTAGE, W4, false, KB, MINW, 2>)
+            : mode == 3 ? (vec ? qgemm_dma<BM, BN, WM, WN, NSTAGE, W4, true, KB, MINW, 3>
+                               : qgemm_dma<BM, BN, WM, WN, NSTAGE, W4, false, KB, MINW, 3>)
                         : (vec ? qgemm_dma<BM, BN, WM, WN, NSTAGE, W4, true, KB, MINW, 0>
                                : qgemm_dma<BM, BN, WM, WN, NSTAGE, W4, false, KB, MINW, 0>);
-  static bool attr_set[6] = {false, false, false, false, false, false};  // dynamic LDS above 64 KiB has to be allowed once per kernel
+  static bool attr_set[8] = {false, false, false, false, false, false, false, false};  // dynamic LDS above 64 KiB has to be allowed once per kernel
   const int which = mode * 2 + (vec ? 1 : 0);
   if (!attr_set[which]) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -816,8 +867,8 @@ static int run_qgemm(const int8_t* a_q, const void* w_q, int w_storage_bits, int
                      int32_t* acc_out, EpiArgs epi, int64_t* n_partials, hipStream_t st) {
   const float* y_ref = epi.yref;
   if (!a_q || !w_q) return MPQ_ERR_NULL;
-  if (!y_out && !acc_out && !y_ref) return MPQ_ERR_NULL;
-  if ((y_out || y_ref) && (!a_scale || !w_scale)) return MPQ_ERR_NULL;
+  if (!y_out && !acc_out && !y_ref && !epi.amax && !epi.codes) return MPQ_ERR_NULL;
+  if ((y_out || y_ref || epi.amax || epi.codes) && (!a_scale || !w_scale)) return MPQ_ERR_NULL;
   if (w_storage_bits != 8 && w_storage_bits != 4) return MPQ_ERR_BITS;
   if (M <= 0 || N <= 0 || K <= 0) return MPQ_ERR_SHAPE;
   if (K > 133143) return MPQ_ERR_SHAPE;  // K * 127 * 127 must stay below 2^31
@@ -883,13 +934,13 @@ extern "C" int mpq_qgemm(const int8_t* a_q, const void* w_q, int w_storage_bits,
   (void)ws_bytes;
   if (!y_out && !acc_out) return MPQ_ERR_NULL;
   return run_qgemm(a_q, w_q, w_storage_bits, M, N, K, a_scale, w_scale, w_gran, y_out, acc_out,
-                   EpiArgs{nullptr, nullptr, 0, nullptr}, nullptr, (hipStream_t)stream);
+                   kNoEpi, nullptr, (hipStream_t)stream);
 }
 
 extern "C" int mpq_qgemm_act(const int8_t* a_q, const void* w_q, int w_storage_bits, int64_t M, int64_t N,
                              int64_t K, const float* a_scale, const float* w_scale, int w_gran, int act,
                              float* y_out, float* absmax_out, int accumulate, void* stream) {
-  if (!y_out) return MPQ_ERR_NULL;
+  if (!y_out && !absmax_out) return MPQ_ERR_NULL;
   if (act < MPQ_ACT_NONE || act > MPQ_ACT_GELU) return MPQ_ERR_SHAPE;
   if (absmax_out && (reinterpret_cast<uintptr_t>(absmax_out) & 3u)) return MPQ_ERR_ALIGN;
   hipStream_t st = (hipStream_t)stream;
@@ -901,7 +952,18 @@ extern "C" int mpq_qgemm_act(const int8_t* a_q, const void* w_q, int w_storage_b
   if (w_gran != MPQ_PER_TENSOR && w_gran != MPQ_PER_ROW) return MPQ_ERR_GRAN;
   if (amax && !accumulate) fill_u32_k<<<1, 1, 0, st>>>(amax, 0u);
   return run_qgemm(a_q, w_q, w_storage_bits, M, N, K, a_scale, w_scale, w_gran, y_out, nullptr,
-                   EpiArgs{nullptr, nullptr, act, amax}, nullptr, st);
+                   EpiArgs{nullptr, nullptr, act, amax, nullptr, 0, nullptr}, nullptr, st);
+}
+
+extern "C" int mpq_qgemm_act_codes(const int8_t* a_q, const void* w_q, int w_storage_bits, int64_t M, int64_t N,
+                                   int64_t K, const float* a_scale, const float* w_scale, int w_gran, int act,
+                                   const float* absmax, int bits, int8_t* codes_out, void* stream) {
+  if (!absmax || !codes_out) return MPQ_ERR_NULL;
+  if (act < MPQ_ACT_NONE || act > MPQ_ACT_GELU) return MPQ_ERR_SHAPE;
+  if (bits < 2 || bits > 8) return MPQ_ERR_BITS;
+  if (reinterpret_cast<uintptr_t>(absmax) & 3u) return MPQ_ERR_ALIGN;
+  return run_qgemm(a_q, w_q, w_storage_bits, M, N, K, a_scale, w_scale, w_gran, nullptr, nullptr,
+                   EpiArgs{nullptr, nullptr, act, nullptr, absmax, bits, codes_out}, nullptr, (hipStream_t)stream);
 }
 
 extern "C" size_t mpq_qgemm_score_workspace_bytes(int64_t M, int64_t N, int64_t K, int w_storage_bits) {
@@ -923,7 +985,7 @@ extern "C" int mpq_qgemm_score(const int8_t* a_q, const void* w_q, int w_storage
   double* partials = reinterpret_cast<double*>(ws);
   int64_t count = 0;
   const int rc = run_qgemm(a_q, w_q, w_storage_bits, M, N, K, a_scale, w_scale, w_gran, y_out, nullptr,
-                           EpiArgs{y_ref, partials, 0, nullptr}, &count, st);
+                           EpiArgs{y_ref, partials, 0, nullptr, nullptr, 0, nullptr}, &count, st);
   if (rc != MPQ_OK) return rc;
   sum_partials_k<<<1, kBlock, 0, st>>>(partials, count, sse_out);
   return launch_status();

@@ -23,7 +23,7 @@ EXPORTS = [
     "mpq_quant_error", "mpq_noise_inject", "mpq_qgemm_workspace_bytes", "mpq_qgemm",
     "mpq_sse_pair_workspace_bytes", "mpq_sse_pair", "mpq_qgemm_score_workspace_bytes", "mpq_qgemm_score",
     "mpq_search_bisection", "mpq_search_greedy", "mpq_noise_inject_sweep",
-    "mpq_fake_quant_scales", "mpq_scale_grad_workspace_bytes", "mpq_scale_grad", "mpq_scale_sgd_step", "mpq_qgemm_act",
+    "mpq_fake_quant_scales", "mpq_scale_grad_workspace_bytes", "mpq_scale_grad", "mpq_scale_sgd_step", "mpq_qgemm_act", "mpq_qgemm_act_codes",
 ]
 
 ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
@@ -77,6 +77,7 @@ def lib():
         L.mpq_scale_grad.argtypes = [vp, i64, i64, ci, vp, vp, ci, vp, vp, vp, vp, vp, sz, vp]
         L.mpq_scale_sgd_step.argtypes = [vp, vp, vp, vp, i64, C.c_double, vp]
         L.mpq_qgemm_act.argtypes = [vp, vp, ci, i64, i64, i64, vp, vp, ci, ci, vp, vp, ci, vp]
+        L.mpq_qgemm_act_codes.argtypes = [vp, vp, ci, i64, i64, i64, vp, vp, ci, ci, vp, ci, vp, vp]
         L.mpq_qgemm_workspace_bytes.restype = sz
         L.mpq_qgemm_workspace_bytes.argtypes = [i64, i64, i64, ci]
         L.mpq_qgemm.argtypes = [vp, vp, ci, i64, i64, i64, vp, vp, ci, vp, vp, vp, sz, vp]
@@ -376,14 +377,15 @@ def scale_sgd_step(inv, scale, dinv, dscale, lr):
 
 
 def qgemm_act(a_q, w_q, a_scale, w_scale, act, w_storage_bits=8, w_gran=PER_TENSOR, y=None, absmax=None,
-              want_absmax=True, accumulate=False):
+              want_absmax=True, accumulate=False, want_y=True):
     """One quantized layer with its activation (ACT_RELU / ACT_GELU) applied in the epilogue and,
-    if wanted, the absmax of the activated output.  Returns (Y, absmax float32[1] | None)."""
+    if wanted, the absmax of the activated output.  Returns (Y | None, absmax float32[1] | None);
+    want_y=False is the calibration-only pass that stores no layer output."""
     torch = _torch()
     a_q = _dev2d(a_q, torch.int8)
     M, K = a_q.shape
     N = w_q.shape[0]
-    if y is None:
+    if y is None and want_y:
         y = torch.empty((M, N), dtype=torch.float32, device=a_q.device)
     if want_absmax and absmax is None:
         if accumulate:
@@ -392,3 +394,18 @@ def qgemm_act(a_q, w_q, a_scale, w_scale, act, w_storage_bits=8, w_gran=PER_TENS
     _check(lib().mpq_qgemm_act(_ptr(a_q), _ptr(w_q), w_storage_bits, M, N, K, _ptr(a_scale), _ptr(w_scale), w_gran,
                                int(act), _ptr(y), _ptr(absmax), 1 if accumulate else 0, _stream()), "mpq_qgemm_act")
     return y, absmax
+
+
+def qgemm_act_codes(a_q, w_q, a_scale, w_scale, act, absmax, bits, w_storage_bits=8, w_gran=PER_TENSOR, codes=None):
+    """The layer of qgemm_act with its activated output quantized in the epilogue (Eq. 1 with the
+    given absmax): returns the int8 codes [M x N]; the fp32 output is never stored."""
+    torch = _torch()
+    a_q = _dev2d(a_q, torch.int8)
+    M, K = a_q.shape
+    N = w_q.shape[0]
+    if codes is None:
+        codes = torch.empty((M, N), dtype=torch.int8, device=a_q.device)
+    _check(lib().mpq_qgemm_act_codes(_ptr(a_q), _ptr(w_q), w_storage_bits, M, N, K, _ptr(a_scale), _ptr(w_scale),
+                                     w_gran, int(act), _ptr(absmax), int(bits), _ptr(codes), _stream()),
+           "mpq_qgemm_act_codes")
+    return codes

@@ -184,6 +184,28 @@ def test_qgemm_score_validation():
 
 
 @needs_no_gpu
+def test_qgemm_act_and_act_codes_validation():
+    L = mpq.lib()
+    f = L.mpq_qgemm_act
+    head = (FAKE16, FAKE16, 8, 256, 256, 64, FAKE, FAKE, 0)
+    assert f(*head, 1, None, None, 0, None) == mpq.ERR_NULL                       # neither output
+    assert f(*head, 3, FAKE16, None, 0, None) == mpq.ERR_SHAPE                    # unknown activation
+    assert f(*head, 1, FAKE16, C.c_void_p(0x10002), 0, None) == mpq.ERR_ALIGN
+    assert f(None, FAKE16, 8, 256, 256, 64, FAKE, FAKE, 0, 1, None, FAKE16, 0, None) == mpq.ERR_NULL
+    assert f(FAKE16, FAKE16, 6, 256, 256, 64, FAKE, FAKE, 0, 1, None, FAKE16, 0, None) == mpq.ERR_BITS
+    g = L.mpq_qgemm_act_codes
+    assert g(*head, 1, None, 8, FAKE16, None) == mpq.ERR_NULL                     # no absmax
+    assert g(*head, 1, FAKE16, 8, None, None) == mpq.ERR_NULL                     # no codes_out
+    assert g(*head, 1, FAKE16, 9, FAKE16, None) == mpq.ERR_BITS
+    assert g(*head, 1, FAKE16, 1, FAKE16, None) == mpq.ERR_BITS
+    assert g(*head, 5, FAKE16, 8, FAKE16, None) == mpq.ERR_SHAPE
+    assert g(*head, 1, C.c_void_p(0x10002), 8, FAKE16, None) == mpq.ERR_ALIGN
+    assert g(FAKE16, FAKE16, 8, 256, 0, 64, FAKE, FAKE, 0, 1, FAKE16, 8, FAKE16, None) == mpq.ERR_SHAPE
+    assert g(FAKE16, FAKE16, 8, 256, 256, 64, None, FAKE, 0, 1, FAKE16, 8, FAKE16, None) == mpq.ERR_NULL
+    assert g(FAKE16, FAKE16, 4, 256, 256, 63, FAKE, FAKE, 0, 1, FAKE16, 8, FAKE16, None) == mpq.ERR_SHAPE
+
+
+@needs_no_gpu
 def test_scale_adjust_validation():
     L = mpq.lib()
     assert L.mpq_scale_grad_workspace_bytes(64, 64, 0) > 0

@@ -163,6 +163,14 @@ def test_config5_candidate_scoring_chain():
         gelu_o = oracle.activation(h_o, oracle.ACT_GELU)
         assert (np.abs(hf_h[rows] - gelu_o) <= 2e-5 * np.abs(gelu_o) + 2e-7 * np.abs(h_o)).all()
         assert host(am_f)[0] == np.abs(hf_h).max()
+        # the two-pass form: calibration-only pass, then Eq. 1 in the epilogue; no fp32 output stored
+        sx1, sw1 = mpq.scale_from_absmax(am_x, ba1), mpq.scale_from_absmax(am_w1, bw1)
+        _, am_2 = mpq.qgemm_act(cx, cw1, sx1, sw1, mpq.ACT_GELU, st1, want_y=False)
+        assert host(am_2)[0] == host(am_f)[0]
+        ch = mpq.qgemm_act_codes(cx, cw1, sx1, sw1, mpq.ACT_GELU, am_2, ba2, st1)
+        _, ch_o, _ = oracle.fake_quant(hf_h[rows], host(am_2), ba2)
+        np.testing.assert_array_equal(host(ch)[rows], ch_o)
+        del ch
         g = t.nn.functional.gelu(h)  # not a libmpq call: the same tensor goes to both sides
         g_h = host(g)
         am_g = mpq.calibrate_absmax(g)

@@ -395,6 +395,56 @@ def test_qgemm_act_matches_the_composition(mnk, wbits, act):
     np.testing.assert_array_equal(host(y), y_h if False else host(mpq.qgemm_act(dev(a), dev(ws), dev(sa), dev(sw), act, wbits, mpq.PER_ROW)[0]))
 
 
+# ------------------------------------------------------- qgemm + activation + Eq. 1 in the epilogue
+@pytest.mark.parametrize("mnk,wbits", [((64, 256, 256), 8), ((33, 31, 130), 8), ((300, 70, 48), 4), ((2048, 2048, 384), 8),
+                                        ((4100, 4092, 160), 4), ((2085, 2046, 112), 8), ((6272, 256, 512), 4),
+                                        ((12288, 768, 128), 4)])
+@pytest.mark.parametrize("act,bits", [(0, 8), (1, 8), (1, 4), (2, 8), (2, 4), (2, 2)])
+def test_qgemm_act_codes_are_the_fake_quant_codes_of_the_activated_output(mnk, wbits, act, bits):
+    """Two passes over the product: the calibration-only pass must find the absmax the storing pass
+    finds, and the codes pass must give bit for bit what Eq. 1 gives on the fp32 output.  The oracle
+    quantizes the GPU's own fp32 output (a stage of a chain is checked on the stage's own input);
+    against the oracle's end-to-end composition codes may differ only where the pre-rounding value
+    sits on a rounding boundary within the layer output's tolerance."""
+    M, N, K = mnk
+    q = 127 if wbits == 8 else 7
+    a, w = rand_codes((M, K), 127, 70), rand_codes((N, K), q, 71)
+    ws = w if wbits == 8 else oracle.pack4(w)
+    r = np.random.Generator(np.random.PCG64(72))
+    sa = np.array([0.002], np.float32)
+    sw = (r.random(N).astype(np.float32) + 0.5) * np.float32(1e-3)
+    for mk in (dev, dev_misaligned):
+        da, dw, dsa, dsw = mk(a), mk(ws), dev(sa), dev(sw)
+        y, am = mpq.qgemm_act(da, dw, dsa, dsw, act, wbits, mpq.PER_ROW)
+        none, am_only = mpq.qgemm_act(da, dw, dsa, dsw, act, wbits, mpq.PER_ROW, want_y=False)
+        assert none is None and host(am_only)[0] == host(am)[0]
+        codes = host(mpq.qgemm_act_codes(da, dw, dsa, dsw, act, am, bits, wbits, mpq.PER_ROW))
+        y_h, am_h = host(y), host(am)
+        _, want, _ = oracle.fake_quant(y_h, am_h, bits)
+        np.testing.assert_array_equal(codes, want)
+    # end to end against the oracle alone
+    y_o, am_o = oracle.qgemm_act(a, ws, sa, sw, act, wbits, oracle.PER_ROW)
+    _, want_o, _ = oracle.fake_quant(y_o, am_o, bits)
+    diff = codes.astype(np.int32) - want_o
+    if diff.any():
+        _, inv = oracle.bit_constants(float(am_o[0]), bits)
+        p = y_o.astype(np.float64) * float(inv)
+        off_boundary = np.abs(p - np.floor(p) - 0.5)
+        bad = diff != 0
+        assert np.abs(diff).max() <= 1
+        assert (off_boundary[bad] <= 1e-4 * np.maximum(1.0, np.abs(p[bad]))).all()
+        assert bad.mean() < 1e-3
+    # a foreign absmax smaller than the data saturates at +-qmax; zero gives zero codes
+    small = dev(np.array([am_h[0] / 4], np.float32))
+    sat = host(mpq.qgemm_act_codes(dev(a), dev(ws), dev(sa), dev(sw), act, small, bits, wbits, mpq.PER_ROW))
+    _, want_sat, _ = oracle.fake_quant(y_h, host(small), bits)
+    np.testing.assert_array_equal(sat, want_sat)
+    qmax = (1 << (bits - 1)) - 1
+    assert sat.max() <= qmax and sat.min() >= -qmax
+    zero = host(mpq.qgemm_act_codes(dev(a), dev(ws), dev(sa), dev(sw), act, dev(np.zeros(1, np.float32)), bits, wbits, mpq.PER_ROW))
+    assert not zero.any()
+
+
 # ---------------------------------------------------------------------------------- sse pair
 @pytest.mark.parametrize("n", [1, 7, 4096, 100003, 1 << 20])
 def test_sse_pair(n):
