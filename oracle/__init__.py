@@ -217,6 +217,36 @@ def sse_pair(y, y_ref) -> float:
     return float(lib().orc_sse_pair(_p(y), _p(r), C.c_int64(y.size)))
 
 
+def rademacher(seed: int, stream_id: int, rows: int, cols: int):
+    """Random signs for Hutchinson's estimator (Sec. 3.2.3): float32 [rows x cols] of +-1."""
+    v = np.empty((rows, cols), np.float32)
+    rc = lib().orc_rademacher(C.c_uint64(seed), C.c_uint64(stream_id), C.c_int64(rows), C.c_int64(cols), _p(v))
+    assert rc == 0
+    return v
+
+
+def hutchinson_quad(x, v):
+    """quad[p] = ||X v_p||^2 for the rows v_p of v: the quadratic forms of Hutchinson's estimator
+    for a linear layer under a mean-squared-error loss (Sec. 3.2.3).  float64 [P]."""
+    x, v = _f32_2d(x), _f32_2d(v)
+    assert x.shape[1] == v.shape[1]
+    q = np.empty(v.shape[0], np.float64)
+    rc = lib().orc_hutchinson_quad(_p(x), C.c_int64(x.shape[0]), C.c_int64(x.shape[1]), _p(v),
+                                   C.c_int64(v.shape[0]), _p(q))
+    assert rc == 0
+    return q
+
+
+def hutchinson_trace(x, v):
+    """Estimate of Tr(H) of the layer loss with respect to the weights, (2 / M) mean_p ||X v_p||^2,
+    and the standard error of that mean."""
+    q = hutchinson_quad(x, v)
+    m = _f32_2d(x).shape[0]
+    est = 2.0 / m * q.mean()
+    err = 2.0 / m * q.std(ddof=1) / np.sqrt(q.size) if q.size > 1 else float("nan")
+    return float(est), float(err)
+
+
 def fake_quant_scales(x, inv, scale, bits, gran=PER_TENSOR):
     """Eq. 1 with explicit scales: returns (Q fp32, codes int8)."""
     x = _f32_2d(x)

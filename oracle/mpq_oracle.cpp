@@ -23,6 +23,10 @@
 //   orc_fake_quant_scales, orc_scale_grad, orc_scale_sgd_step
 //                       Sec. 3.1, adjustment step: Eq. 1 with its two scales as free parameters,
 //                       their straight-through gradients, one gradient-descent step on them.
+//   orc_rademacher, orc_hutchinson_quad
+//                       Sec. 3.2.3: Hutchinson's estimate of the trace of the Hessian, for one
+//                       linear layer under a mean-squared-error loss: random sign vectors and the
+//                       quadratic forms v' H v they give.
 //
 // Parity status: every function here is pinned by tests (brute force, exact rational arithmetic,
 // closed forms, invariants, published Philox known-answer vectors).  Nothing is "parity unpinned".
@@ -370,6 +374,54 @@ double orc_sse_pair(const float* y, const float* y_ref, int64_t n) {
     s += d * d;
   }
   return s;
+}
+
+// ------------------------------------------------------------------------------------------
+// Sec. 3.2.3, E_Hessian = E[Tr(d^2 L / d w_i^2)], the trace estimated with Hutchinson's algorithm:
+// Tr(H) = E_v[v' H v] for random v with independent zero-mean unit-variance entries; the usual
+// choice, taken here, is random signs.
+//
+// The one case with no network behind it: a linear layer Y = X W' (X [M x K], W [N x K]) under
+// L = mean over the M N outputs of (Y - T)^2.  L is quadratic in W; its Hessian with respect to
+// vec(W) is (2 / (M N)) (I_N (x) X'X), whatever W and T are.  For a probe V [N x K] that is
+// v' H v = (2 / (M N)) sum_n || X v_n ||^2: every row of V is one K-vector v_n that meets the same
+// block X'X, so probes are drawn as a list of K-vectors and
+//     Tr(H) ~= (2 / (M N)) * N * mean_p || X v_p ||^2 = (2 / M) mean_p || X v_p ||^2,
+// against the exact Tr(H) = (2 / M) ||X||_F^2.  (With respect to X instead, the roles swap:
+// quadratic forms of W, trace (2 / N) ||W||_F^2.)
+//
+// Random signs: element e = r * cols + c of the [rows x cols] sign matrix is decided by bit
+// (e mod 128) of the Philox-4x32-10 block with counter (e / 128 lo, hi, stream lo, stream hi) and
+// key (seed lo, seed hi XOR 0x5241444D): bit t sits in word t / 32 at position t mod 32; a set
+// bit gives -1, a clear bit +1.  (The constant keeps these draws apart from the Gaussian stream
+// of the same seed and stream id.)
+int orc_rademacher(uint64_t seed, uint64_t stream_id, int64_t rows, int64_t cols, float* v) {
+  if (!v || rows <= 0 || cols <= 0) return ORC_BAD_ARG;
+  const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32) ^ 0x5241444Du};
+  for (int64_t e = 0; e < rows * cols; ++e) {
+    const uint64_t g = (uint64_t)e >> 7;
+    const uint32_t ctr[4] = {(uint32_t)g, (uint32_t)(g >> 32), (uint32_t)stream_id, (uint32_t)(stream_id >> 32)};
+    uint32_t w[4];
+    orc_philox4x32_10(ctr, key, w);
+    const unsigned t = (unsigned)(e & 127);
+    v[e] = ((w[t >> 5] >> (t & 31u)) & 1u) ? -1.0f : 1.0f;
+  }
+  return ORC_OK;
+}
+
+// quad[p] = || X v_p ||^2 = sum_m (sum_k X[m][k] v[p][k])^2, in double, index order.
+int orc_hutchinson_quad(const float* x, int64_t M, int64_t K, const float* v, int64_t P, double* quad) {
+  if (!x || !v || !quad || M <= 0 || K <= 0 || P <= 0) return ORC_BAD_ARG;
+  for (int64_t p = 0; p < P; ++p) {
+    double q = 0.0;
+    for (int64_t m = 0; m < M; ++m) {
+      double s = 0.0;
+      for (int64_t k = 0; k < K; ++k) s += (double)x[m * K + k] * (double)v[p * K + k];
+      q += s * s;
+    }
+    quad[p] = q;
+  }
+  return ORC_OK;
 }
 
 // ------------------------------------------------------------------------------------------
