@@ -172,6 +172,28 @@ int mpq_qgemm_act_codes(const int8_t* a_q, const void* w_q, int w_storage_bits, 
                         int64_t K, const float* a_scale, const float* w_scale, int w_gran, int act,
                         const float* absmax, int bits, int8_t* codes_out, void* stream);
 
+/* ---- Hutchinson's estimate of the Hessian trace (Sec. 3.2.3, E_Hessian) ------------------------
+ * For a linear layer Y = X W' (X [M x K], W [N x K]) under L = mean over the M N outputs of
+ * (Y - T)^2 the Hessian with respect to W is (2 / (M N)) (I_N (x) X'X): a probe's quadratic form
+ * is a sum of ||X v||^2 over K-vectors v, and
+ *     Tr(H) ~= (2 / M) * mean_p quad[p],   quad[p] = ||X v_p||^2   (exact: (2 / M) ||X||_F^2).
+ * With respect to the layer input instead, pass W as x: Tr = (2 / N) * mean_p ||W v_p||^2.
+ *
+ * mpq_rademacher: v_out fp32 [rows x cols] of +1 / -1.  Element e = r * cols + c takes bit
+ *   (e mod 128) of the Philox-4x32-10 block with counter (e / 128, stream_id) and key
+ *   (seed lo, seed hi XOR 0x5241444D); bit t = word t / 32, position t mod 32; set bit = -1.
+ *   Depends on (seed, stream_id, e) only.  rows * cols <= 2^38.
+ * mpq_hutchinson_quad: quad_out double [P], quad_out[p] = sum_m (sum_k x[m][k] v[p][k])^2 for any
+ *   fp32 probes v [P x K] (the sums over k are taken in fp32 on the matrix cores, squares and the
+ *   sum over m in fp32 per lane, the final combine in double in a fixed order; reproducible).
+ *   x, v 4-byte aligned (16-byte aligned with K % 4 == 0 takes the vector loads); quad_out 8-byte
+ *   aligned.  M < 2^31, P <= 2^20.  Workspace from the query (MPQ_ERR_WORKSPACE if too small). */
+int mpq_rademacher(uint64_t seed, uint64_t stream_id, int64_t rows, int64_t cols, float* v_out,
+                   void* stream);
+size_t mpq_hutchinson_quad_workspace_bytes(int64_t M, int64_t K, int64_t P);
+int mpq_hutchinson_quad(const float* x, int64_t M, int64_t K, const float* v, int64_t P,
+                        double* quad_out, void* ws, size_t ws_bytes, void* stream);
+
 /* ---- "Evaluate f(x, w) and save accuracy a" of Alg. 1 / Alg. 2 in one call -------------------
  * The layer of mpq_qgemm with the score of mpq_sse_pair taken in its epilogue:
  * sse_out[0] = sum_{m,n} (y[m][n] - y_ref[m][n])^2 (double), y exactly as mpq_qgemm defines it.

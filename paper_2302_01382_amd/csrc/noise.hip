@@ -14,28 +14,9 @@
 // One lane produces one group of four normals (one Philox call).  8 bytes of HBM traffic per
 // element; ~45 integer + ~25 fp32 lane-operations per element.
 #include "common.hpp"
+#include "philox.hpp"
 
 namespace mpq {
-
-struct U4 { unsigned a, b, c, d; };
-
-__device__ __forceinline__ U4 philox4x32_10(unsigned c0, unsigned c1, unsigned c2, unsigned c3,
-                                            unsigned k0, unsigned k1) {
-#pragma unroll
-  for (int round = 0; round < 10; ++round) {
-    const unsigned long long p0 = (unsigned long long)0xD2511F53u * c0;
-    const unsigned long long p1 = (unsigned long long)0xCD9E8D57u * c2;
-    const unsigned n0 = (unsigned)(p1 >> 32) ^ c1 ^ k0;
-    const unsigned n2 = (unsigned)(p0 >> 32) ^ c3 ^ k1;
-    c1 = (unsigned)p1;
-    c3 = (unsigned)p0;
-    c0 = n0;
-    c2 = n2;
-    k0 += 0x9E3779B9u;
-    k1 += 0xBB67AE85u;
-  }
-  return U4{c0, c1, c2, c3};
-}
 
 // -2 ln(k 2^-24), 1 <= k <= 2^24
 __device__ __forceinline__ float neg2log_u24(unsigned k) {

@@ -24,6 +24,7 @@ EXPORTS = [
     "mpq_sse_pair_workspace_bytes", "mpq_sse_pair", "mpq_qgemm_score_workspace_bytes", "mpq_qgemm_score",
     "mpq_search_bisection", "mpq_search_greedy", "mpq_noise_inject_sweep",
     "mpq_fake_quant_scales", "mpq_scale_grad_workspace_bytes", "mpq_scale_grad", "mpq_scale_sgd_step", "mpq_qgemm_act", "mpq_qgemm_act_codes",
+    "mpq_rademacher", "mpq_hutchinson_quad_workspace_bytes", "mpq_hutchinson_quad",
 ]
 
 ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
@@ -78,6 +79,10 @@ def lib():
         L.mpq_scale_sgd_step.argtypes = [vp, vp, vp, vp, i64, C.c_double, vp]
         L.mpq_qgemm_act.argtypes = [vp, vp, ci, i64, i64, i64, vp, vp, ci, ci, vp, vp, ci, vp]
         L.mpq_qgemm_act_codes.argtypes = [vp, vp, ci, i64, i64, i64, vp, vp, ci, ci, vp, ci, vp, vp]
+        L.mpq_rademacher.argtypes = [C.c_uint64, C.c_uint64, i64, i64, vp, vp]
+        L.mpq_hutchinson_quad_workspace_bytes.argtypes = [i64, i64, i64]
+        L.mpq_hutchinson_quad_workspace_bytes.restype = C.c_size_t
+        L.mpq_hutchinson_quad.argtypes = [vp, i64, i64, vp, i64, vp, vp, C.c_size_t, vp]
         L.mpq_qgemm_workspace_bytes.restype = sz
         L.mpq_qgemm_workspace_bytes.argtypes = [i64, i64, i64, ci]
         L.mpq_qgemm.argtypes = [vp, vp, ci, i64, i64, i64, vp, vp, ci, vp, vp, vp, sz, vp]
@@ -271,6 +276,38 @@ def sse_pair(y, y_ref, out=None, ws: Workspace = None):
         out = torch.empty(1, dtype=torch.float64, device=y.device)
     wp, wn = (ws or _default_ws).get(sse_pair_workspace_bytes(n))
     _check(lib().mpq_sse_pair(_ptr(y), _ptr(y_ref), n, _ptr(out), wp, wn, _stream()), "mpq_sse_pair")
+    return out
+
+
+def rademacher(seed: int, stream_id: int, rows: int, cols: int, out=None, device=None):
+    """Random signs (+1 / -1, fp32 [rows x cols]) for Hutchinson's estimator, one Philox bit each."""
+    torch = _torch()
+    if out is None:
+        out = torch.empty((rows, cols), dtype=torch.float32, device=device or torch.device("cuda", torch.cuda.current_device()))
+    elif out.dtype != torch.float32 or not out.is_contiguous() or out.numel() != rows * cols:
+        raise ValueError("rademacher needs a contiguous fp32 output of rows * cols elements")
+    _check(lib().mpq_rademacher(seed & (2 ** 64 - 1), stream_id & (2 ** 64 - 1), rows, cols, _ptr(out), _stream()),
+           "mpq_rademacher")
+    return out
+
+
+def hutchinson_quad_workspace_bytes(M, K, P) -> int:
+    return int(lib().mpq_hutchinson_quad_workspace_bytes(M, K, P))
+
+
+def hutchinson_quad(x, v, out=None, ws: Workspace = None):
+    """quad[p] = ||X v_p||^2 for the rows v_p of v (float64 [P]): the quadratic forms of Hutchinson's
+    trace estimate for a linear layer under a mean-squared-error loss."""
+    torch = _torch()
+    x, v = _dev2d(x, torch.float32), _dev2d(v, torch.float32)
+    M, K = x.shape
+    P = v.shape[0]
+    if v.shape[1] != K:
+        raise ValueError("probes need as many columns as x")
+    if out is None:
+        out = torch.empty(P, dtype=torch.float64, device=x.device)
+    wp, wn = (ws or _default_ws).get(hutchinson_quad_workspace_bytes(M, K, P))
+    _check(lib().mpq_hutchinson_quad(_ptr(x), M, K, _ptr(v), P, _ptr(out), wp, wn, _stream()), "mpq_hutchinson_quad")
     return out
 
 

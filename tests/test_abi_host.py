@@ -206,6 +206,29 @@ def test_qgemm_act_and_act_codes_validation():
 
 
 @needs_no_gpu
+def test_hutchinson_validation_and_workspace_query():
+    L = mpq.lib()
+    r = L.mpq_rademacher
+    assert r(1, 2, 4, 4, None, None) == mpq.ERR_NULL
+    assert r(1, 2, 0, 4, FAKE16, None) == mpq.ERR_SHAPE
+    assert r(1, 2, 1 << 20, 1 << 19, FAKE16, None) == mpq.ERR_SHAPE          # more than 2^38 elements
+    f = L.mpq_hutchinson_quad
+    need = L.mpq_hutchinson_quad_workspace_bytes(16384, 1024, 32)
+    assert need >= 512 * 32 * 4 and L.mpq_hutchinson_quad_workspace_bytes(0, 4, 4) == 0
+    assert L.mpq_hutchinson_quad_workspace_bytes(16384, 1024, 300) >= 512 * 128 * 4
+    assert f(None, 64, 64, FAKE16, 32, FAKE16, FAKE16, need, None) == mpq.ERR_NULL
+    assert f(FAKE16, 64, 64, None, 32, FAKE16, FAKE16, need, None) == mpq.ERR_NULL
+    assert f(FAKE16, 64, 64, FAKE16, 32, None, FAKE16, need, None) == mpq.ERR_NULL
+    assert f(FAKE16, 0, 64, FAKE16, 32, FAKE16, FAKE16, need, None) == mpq.ERR_SHAPE
+    assert f(FAKE16, 64, 64, FAKE16, 0, FAKE16, FAKE16, need, None) == mpq.ERR_SHAPE
+    assert f(FAKE16, 64, 64, FAKE16, (1 << 20) + 1, FAKE16, FAKE16, need, None) == mpq.ERR_SHAPE
+    assert f(C.c_void_p(0x10002), 64, 64, FAKE16, 32, FAKE16, FAKE16, need, None) == mpq.ERR_ALIGN
+    assert f(FAKE16, 64, 64, FAKE16, 32, C.c_void_p(0x10004), FAKE16, need, None) == mpq.ERR_ALIGN
+    assert f(FAKE16, 16384, 1024, FAKE16, 32, FAKE16, None, 0, None) == mpq.ERR_WORKSPACE
+    assert f(FAKE16, 16384, 1024, FAKE16, 32, FAKE16, FAKE16, need - 4, None) == mpq.ERR_WORKSPACE
+
+
+@needs_no_gpu
 def test_scale_adjust_validation():
     L = mpq.lib()
     assert L.mpq_scale_grad_workspace_bytes(64, 64, 0) > 0
