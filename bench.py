@@ -23,6 +23,7 @@ Other workloads (the parity-test configurations, measured with the same machiner
            cfg5-unfused: mpq_qgemm, torch GELU, mpq_calibrate_absmax, mpq_sse_pair)
     search  Alg. 1 / Alg. 2 over a 24-layer stack, evaluations per second
     latency qgemm latency table at batch 1 and the mixed-precision latency estimate built from it
+    hutchinson  Hessian-trace probe (random sign vectors, quadratic forms on the fp32 matrix cores)
 All inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 """
 from __future__ import annotations
@@ -567,6 +568,91 @@ def run_search(torch, mpq, workloads, args):
     print(json.dumps(out))
 
 
+def run_hutchinson(torch, mpq, workloads, args):
+    """Hessian-trace sensitivity (Sec. 3.2.3) of the BERT-large FFN block's two layers at M = 16384:
+    a step takes the quadratic forms of 32 random sign vectors per tensor, drawn inside the kernel
+    (mpq_hutchinson_quad_signs), for the activation tensors X [16384 x 1024] and GELU(H) [16384 x 4096].
+    Five copies of the pair are rotated through so that no step finds its tensors in the 256 MB
+    memory-side cache.  Also timed: 64 probes (the width at which the fp32 matrix rate is level with
+    the read of the tensor)."""
+    x, w1, _ = workloads.cfg5_tensors()
+    dx = torch.from_numpy(x).cuda()
+    dh = torch.nn.functional.gelu(dx @ torch.from_numpy(w1).cuda().t())
+    copies = [(dx.clone(), dh.clone()) for _ in range(5)]
+    M = dx.shape[0]
+    ws = mpq.Workspace()
+    ws.get(1 << 22)
+    out_q = {}
+
+    def step(i, probes, matrix, timed=None):
+        for j, t in enumerate(copies[i % len(copies)]):
+            K = t.shape[1]
+            key = (probes, K)
+            if key not in out_q:
+                out_q[key] = (torch.empty((probes, K), dtype=torch.float32, device=t.device),
+                              torch.empty(probes, dtype=torch.float64, device=t.device))
+            v, q = out_q[key]
+            if matrix:
+                mpq.rademacher(7, 2 * i + j, probes, K, out=v)
+            if timed is not None:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+            if matrix:
+                mpq.hutchinson_quad(t, v, out=q, ws=ws)
+            else:
+                mpq.hutchinson_quad_signs(t, 7, 2 * i + j, probes, out=q, ws=ws)
+            if timed is not None:
+                e1.record()
+                timed.append((j, e0, e1))
+
+    res = {}
+    for probes, matrix in ((32, False), (64, False), (32, True), (64, True)):
+        for i in range(args.warmup):
+            step(i, probes, matrix)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(i, probes, matrix)
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) / args.steps
+        timed = []
+        for i in range(args.steps):
+            torch.cuda._sleep(2_000_000)
+            step(i, probes, matrix, timed)
+        torch.cuda.synchronize()
+        per = {0: [], 1: []}
+        for j, e0, e1 in timed:
+            per[j].append(e0.elapsed_time(e1) * 1e-3)
+        res[(probes, matrix)] = {"wall_s": wall, "call_s": {j: sum(v) / len(v) for j, v in per.items()}}
+    nbytes = 4 * (dx.numel() + dh.numel())
+    r32, r64 = res[(32, False)], res[(64, False)]
+    big = dh.numel()
+    flops64 = 2.0 * big * 64
+    est, err = None, None
+    from paper_2302_01382_amd import hessian
+    est, err = hessian.trace_linear_mse(dx, 32, 7, 0, ws)
+    exact = 2.0 / M * float((dx.double() ** 2).sum().item())
+    out = {
+        "metric": "Hessian-trace probe GB/s of activations read (32 random sign vectors per tensor)",
+        "value": nbytes / r32["wall_s"] / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": r32["wall_s"] * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 (fp32 matrix cores, fp32 accumulate)", "data": "synthetic",
+        "config": {"workload": "hutchinson: X [16384 x 1024] and GELU(H) [16384 x 4096] of configuration 5's FFN block, "
+                               "32 probes each, 5 copies rotated (cold memory-side cache)", "step_algorithmic_bytes": nbytes},
+        "roofline": {"bound": "hbm", "achieved": 4.0 * big / r32["call_s"][1] / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": 4.0 * big / r32["call_s"][1] / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "hutchinson_quad, 16384 x 4096, 32 probes", "algorithmic_per_launch": 4.0 * big,
+                     "avg_launch_us": r32["call_s"][1] * 1e6},
+        "probes_64": {"bound": "mfma", "achieved": flops64 / r64["call_s"][1] / 1e12, "peak": 157.3, "unit": "TFLOP/s",
+                      "frac": flops64 / r64["call_s"][1] / 1e12 / 157.3, "avg_launch_us": r64["call_s"][1] * 1e6,
+                      "hbm_gbs": 4.0 * big / r64["call_s"][1] / 1e9, "ms_per_step": r64["wall_s"] * 1e3},
+        "probe_matrix_in_memory": {"probes_32_us": res[(32, True)]["call_s"][1] * 1e6,
+                                   "probes_64_us": res[(64, True)]["call_s"][1] * 1e6},
+        "trace_estimate_x": {"estimate": est, "standard_error": err, "exact": exact},
+    }
+    print(json.dumps(out))
+
+
 def run_latency(torch, mpq, workloads, args):
     """Kernel latency table of mpq_qgemm at inference batch size one (the configured ResNet-50 and
     BERT-base layer shapes with M divided by their batch of 32) and the relative latency /
@@ -599,7 +685,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", choices=["cfg2", "cfg3", "cfg4", "cfg4-unfused", "cfg5", "cfg5-twopass", "cfg5-unfused", "search", "latency"], default="cfg2")
+    ap.add_argument("--workload", choices=["cfg2", "cfg3", "cfg4", "cfg4-unfused", "cfg5", "cfg5-twopass", "cfg5-unfused", "search", "latency", "hutchinson"], default="cfg2")
     ap.add_argument("--cpu-sample-rows", type=int, default=2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -625,6 +711,9 @@ def main():
         return
     if args.workload == "latency":
         run_latency(torch, mpq, workloads, args)
+        return
+    if args.workload == "hutchinson":
+        run_hutchinson(torch, mpq, workloads, args)
         return
     extra = {}
     traffic = None

@@ -193,6 +193,12 @@ int mpq_rademacher(uint64_t seed, uint64_t stream_id, int64_t rows, int64_t cols
 size_t mpq_hutchinson_quad_workspace_bytes(int64_t M, int64_t K, int64_t P);
 int mpq_hutchinson_quad(const float* x, int64_t M, int64_t K, const float* v, int64_t P,
                         double* quad_out, void* ws, size_t ws_bytes, void* stream);
+/* The same quadratic forms for the sign probes mpq_rademacher(seed, stream_id, P, K) would store,
+ * drawn inside the kernel: no probe matrix exists in memory.  Results equal those of
+ * mpq_hutchinson_quad on that matrix up to the fp32 rounding of a different summation order over k.  Needs K % 32 == 0 and x 16-byte aligned
+ * (MPQ_ERR_SHAPE otherwise: draw the matrix and use the call above).  Same workspace query. */
+int mpq_hutchinson_quad_signs(const float* x, int64_t M, int64_t K, uint64_t seed, uint64_t stream_id,
+                              int64_t P, double* quad_out, void* ws, size_t ws_bytes, void* stream);
 
 /* ---- "Evaluate f(x, w) and save accuracy a" of Alg. 1 / Alg. 2 in one call -------------------
  * The layer of mpq_qgemm with the score of mpq_sse_pair taken in its epilogue:

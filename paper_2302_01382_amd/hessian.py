@@ -7,7 +7,8 @@ Tr(H) = E_v[v' H v] needs only quadratic forms of X: with P random sign vectors 
     Tr(H) ~= (2 / M) * mean_p ||X v_p||^2        (exact value: (2 / M) ||X||_F^2),
 
 and with respect to the layer input X the same with W in place of X and N in place of M.  Both the
-probes (mpq_rademacher) and the quadratic forms (mpq_hutchinson_quad) are libmpq calls; only the
+probes (mpq_rademacher, or drawn inside mpq_hutchinson_quad_signs) and the quadratic forms
+(mpq_hutchinson_quad) are libmpq calls; only the
 mean and its standard error over P doubles are taken here.
 """
 from __future__ import annotations
@@ -22,8 +23,11 @@ def trace_linear_mse(x, probes: int = 32, seed: int = 0, stream_id: int = 0, ws:
     sign vectors.  x: device fp32 [M x K] (the layer's input activations; pass the weight matrix
     [N x K] for the trace with respect to the input).  Returns (estimate, standard error)."""
     M, K = x.shape
-    v = mpq.rademacher(seed, stream_id, probes, K, device=x.device)
-    q = mpq.hutchinson_quad(x, v, ws=ws).cpu().numpy()
+    if K % 32 == 0 and x.data_ptr() % 16 == 0:   # the probes are drawn inside the kernel
+        q = mpq.hutchinson_quad_signs(x, seed, stream_id, probes, ws=ws).cpu().numpy()
+    else:
+        v = mpq.rademacher(seed, stream_id, probes, K, device=x.device)
+        q = mpq.hutchinson_quad(x, v, ws=ws).cpu().numpy()
     est = 2.0 / M * float(q.mean())
     err = 2.0 / M * float(q.std(ddof=1)) / math.sqrt(probes) if probes > 1 else float("nan")
     return est, err

@@ -24,7 +24,7 @@ EXPORTS = [
     "mpq_sse_pair_workspace_bytes", "mpq_sse_pair", "mpq_qgemm_score_workspace_bytes", "mpq_qgemm_score",
     "mpq_search_bisection", "mpq_search_greedy", "mpq_noise_inject_sweep",
     "mpq_fake_quant_scales", "mpq_scale_grad_workspace_bytes", "mpq_scale_grad", "mpq_scale_sgd_step", "mpq_qgemm_act", "mpq_qgemm_act_codes",
-    "mpq_rademacher", "mpq_hutchinson_quad_workspace_bytes", "mpq_hutchinson_quad",
+    "mpq_rademacher", "mpq_hutchinson_quad_workspace_bytes", "mpq_hutchinson_quad", "mpq_hutchinson_quad_signs",
 ]
 
 ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
@@ -83,6 +83,7 @@ def lib():
         L.mpq_hutchinson_quad_workspace_bytes.argtypes = [i64, i64, i64]
         L.mpq_hutchinson_quad_workspace_bytes.restype = C.c_size_t
         L.mpq_hutchinson_quad.argtypes = [vp, i64, i64, vp, i64, vp, vp, C.c_size_t, vp]
+        L.mpq_hutchinson_quad_signs.argtypes = [vp, i64, i64, C.c_uint64, C.c_uint64, i64, vp, vp, C.c_size_t, vp]
         L.mpq_qgemm_workspace_bytes.restype = sz
         L.mpq_qgemm_workspace_bytes.argtypes = [i64, i64, i64, ci]
         L.mpq_qgemm.argtypes = [vp, vp, ci, i64, i64, i64, vp, vp, ci, vp, vp, vp, sz, vp]
@@ -308,6 +309,20 @@ def hutchinson_quad(x, v, out=None, ws: Workspace = None):
         out = torch.empty(P, dtype=torch.float64, device=x.device)
     wp, wn = (ws or _default_ws).get(hutchinson_quad_workspace_bytes(M, K, P))
     _check(lib().mpq_hutchinson_quad(_ptr(x), M, K, _ptr(v), P, _ptr(out), wp, wn, _stream()), "mpq_hutchinson_quad")
+    return out
+
+
+def hutchinson_quad_signs(x, seed: int, stream_id: int, probes: int, out=None, ws: Workspace = None):
+    """hutchinson_quad for the sign probes rademacher(seed, stream_id, probes, K) would store, drawn
+    inside the kernel (K % 32 == 0, x 16-byte aligned)."""
+    torch = _torch()
+    x = _dev2d(x, torch.float32)
+    M, K = x.shape
+    if out is None:
+        out = torch.empty(probes, dtype=torch.float64, device=x.device)
+    wp, wn = (ws or _default_ws).get(hutchinson_quad_workspace_bytes(M, K, probes))
+    _check(lib().mpq_hutchinson_quad_signs(_ptr(x), M, K, seed & (2 ** 64 - 1), stream_id & (2 ** 64 - 1), probes,
+                                           _ptr(out), wp, wn, _stream()), "mpq_hutchinson_quad_signs")
     return out
 
 

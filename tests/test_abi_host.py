@@ -215,7 +215,7 @@ def test_hutchinson_validation_and_workspace_query():
     f = L.mpq_hutchinson_quad
     need = L.mpq_hutchinson_quad_workspace_bytes(16384, 1024, 32)
     assert need >= 512 * 32 * 4 and L.mpq_hutchinson_quad_workspace_bytes(0, 4, 4) == 0
-    assert L.mpq_hutchinson_quad_workspace_bytes(16384, 1024, 300) >= 512 * 128 * 4
+    assert L.mpq_hutchinson_quad_workspace_bytes(16384, 1024, 300) >= 512 * 64 * 4
     assert f(None, 64, 64, FAKE16, 32, FAKE16, FAKE16, need, None) == mpq.ERR_NULL
     assert f(FAKE16, 64, 64, None, 32, FAKE16, FAKE16, need, None) == mpq.ERR_NULL
     assert f(FAKE16, 64, 64, FAKE16, 32, None, FAKE16, need, None) == mpq.ERR_NULL
@@ -226,6 +226,11 @@ def test_hutchinson_validation_and_workspace_query():
     assert f(FAKE16, 64, 64, FAKE16, 32, C.c_void_p(0x10004), FAKE16, need, None) == mpq.ERR_ALIGN
     assert f(FAKE16, 16384, 1024, FAKE16, 32, FAKE16, None, 0, None) == mpq.ERR_WORKSPACE
     assert f(FAKE16, 16384, 1024, FAKE16, 32, FAKE16, FAKE16, need - 4, None) == mpq.ERR_WORKSPACE
+    g = L.mpq_hutchinson_quad_signs
+    assert g(None, 64, 64, 1, 2, 32, FAKE16, FAKE16, need, None) == mpq.ERR_NULL
+    assert g(FAKE16, 64, 72, 1, 2, 32, FAKE16, FAKE16, need, None) == mpq.ERR_SHAPE       # K not a multiple of 32
+    assert g(C.c_void_p(0x10004), 64, 64, 1, 2, 32, FAKE16, FAKE16, need, None) == mpq.ERR_SHAPE   # x not 16-byte aligned
+    assert g(FAKE16, 16384, 1024, 1, 2, 32, FAKE16, FAKE16, need - 4, None) == mpq.ERR_WORKSPACE
 
 
 @needs_no_gpu

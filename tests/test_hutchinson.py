@@ -135,7 +135,7 @@ def test_gpu_rademacher_bit_exact(shape):
 
 @pytest.mark.gpu
 @pytest.mark.parametrize("mkp", [(64, 256, 32), (33, 31, 5), (1, 4, 1), (1000, 100, 40), (300, 70, 130), (4100, 1024, 64),
-                                 (2085, 2048, 96), (515, 36, 257), (40000, 64, 32)])
+                                 (2085, 2048, 96), (515, 36, 257), (40000, 64, 32), (100, 96, 70), (37, 32, 3), (200, 1056, 33), (100, 48, 5)])
 def test_gpu_hutchinson_quad_matches_the_oracle(mkp):
     from paper_2302_01382_amd import mpq
     M, K, P = mkp
@@ -148,6 +148,16 @@ def test_gpu_hutchinson_quad_matches_the_oracle(mkp):
     # arbitrary real probes go through the same contraction
     g = rng(22).standard_normal((P, K)).astype(np.float32)
     np.testing.assert_allclose(mpq.hutchinson_quad(dev(x), dev(g)).cpu().numpy(), oracle.hutchinson_quad(x, g), rtol=1e-4)
+    # the sign probes drawn inside the kernel: the same bits as the stored matrix (k is summed in
+    # another order, so the fp32 sums agree to rounding, not bit for bit)
+    if K % 32 == 0:
+        a = mpq.hutchinson_quad_signs(dev(x), 21, 0, P).cpu().numpy()
+        np.testing.assert_allclose(a, want, rtol=1e-4, atol=0)
+        np.testing.assert_allclose(a, mpq.hutchinson_quad(dev(x), mpq.rademacher(21, 0, P, K)).cpu().numpy(), rtol=2e-5)
+        np.testing.assert_array_equal(a, mpq.hutchinson_quad_signs(dev(x), 21, 0, P).cpu().numpy())
+    else:
+        with pytest.raises(mpq.MpqError):
+            mpq.hutchinson_quad_signs(dev(x), 21, 0, P)
     # reproducible bit for bit, and zero for a zero tensor
     a = mpq.hutchinson_quad(dev(x), dev(v)).cpu().numpy()
     np.testing.assert_array_equal(a, mpq.hutchinson_quad(dev(x), dev(v)).cpu().numpy())
