@@ -195,7 +195,7 @@ int mpq_hutchinson_quad(const float* x, int64_t M, int64_t K, const float* v, in
                         double* quad_out, void* ws, size_t ws_bytes, void* stream);
 /* The same quadratic forms for the sign probes mpq_rademacher(seed, stream_id, P, K) would store,
  * drawn inside the kernel: no probe matrix exists in memory.  Results equal those of
- * mpq_hutchinson_quad on that matrix up to the fp32 rounding of a different summation order over k.  Needs K % 32 == 0 and x 16-byte aligned
+ * mpq_hutchinson_quad on that matrix up to the fp32 rounding of a different summation order over k.  Needs K % 16 == 0 and x 16-byte aligned
  * (MPQ_ERR_SHAPE otherwise: draw the matrix and use the call above).  Same workspace query. */
 int mpq_hutchinson_quad_signs(const float* x, int64_t M, int64_t K, uint64_t seed, uint64_t stream_id,
                               int64_t P, double* quad_out, void* ws, size_t ws_bytes, void* stream);

@@ -71,22 +71,24 @@ struct Operands {
   float4 v[PB][CH];
 };
 
-// Where the probes come from: a matrix in memory (chunks of 32 k), or (SIGNS) the sign stream of
-// mpq_rademacher drawn on the spot (chunks of 64 k: with K a multiple of 32 the 32 signs a lane
-// needs for a chunk are exactly one 32-bit Philox word; one Philox call per lane and chunk, about
-// 80 vector operations next to the chunk's 32 matrix steps of 64 clocks each).
+// Where the probes come from: a matrix in memory, or (SIGNS) the sign stream of mpq_rademacher
+// drawn on the spot: with K a multiple of 16 the sixteen signs a lane needs for a chunk are one
+// half of a 32-bit Philox word (one Philox call per lane and chunk, about 80 vector operations
+// next to the chunk's 16 matrix steps of 64 clocks each).  Chunks of 64 k (a whole word per lane)
+// were slower: a lane's run of 128 bytes puts 64 different lines under every load instruction.
 struct Probes {
   const float* V;
   unsigned long long seed, sid, first;  // first: index of probe row 0 of this pass in the sign matrix
 };
 
-// the Philox word that holds the 32 signs starting at element `base` (a multiple of 32) of the sign matrix
+// the sixteen signs starting at element `base` (a multiple of 16) of the sign matrix, in the low bits
 __device__ __forceinline__ unsigned sign_word(const Probes& pr, unsigned long long base) {
   const unsigned long long g = base >> 7;
   const U4 w = philox4x32_10((unsigned)g, (unsigned)(g >> 32), (unsigned)pr.sid, (unsigned)(pr.sid >> 32),
                              (unsigned)pr.seed, (unsigned)(pr.seed >> 32) ^ 0x5241444Du);
   const unsigned sel = (unsigned)(base >> 5) & 3u;
-  return sel == 0 ? w.a : sel == 1 ? w.b : sel == 2 ? w.c : w.d;
+  const unsigned word = sel == 0 ? w.a : sel == 1 ? w.b : sel == 2 ? w.c : w.d;
+  return word >> ((unsigned)base & 16u);
 }
 
 __device__ __forceinline__ float sign_f(unsigned bits, int t) {  // +1.0f, or -1.0f if bit t is set
@@ -113,7 +115,7 @@ __device__ __forceinline__ void load_piece(Operands<PB, CH>& o, int e, const flo
 template <int PB, bool VEC, bool SIGNS>
 __global__ __launch_bounds__(kHW * 64, 4) void hutch_k(const float* __restrict__ X, int64_t M, int64_t K,
                                                        Probes pr, int64_t P, float* __restrict__ part) {
-  constexpr int CH = SIGNS ? 8 : 4;   // pieces per chunk and lane
+  constexpr int CH = 4;               // pieces per chunk and lane
   constexpr int CK = 8 * CH;          // k per chunk
   __shared__ float red[kHW - 1][PB][16][64];
   const int lane = threadIdx.x & 63;
@@ -310,7 +312,7 @@ extern "C" int mpq_hutchinson_quad_signs(const float* x, int64_t M, int64_t K, u
                                          int64_t P, double* quad_out, void* ws, size_t ws_bytes, void* stream) {
   const int rc = check_hutchinson(x, M, K, P, quad_out, ws, ws_bytes);
   if (rc != MPQ_OK) return rc;
-  if ((K & 31) || !aligned16(x)) return MPQ_ERR_SHAPE;  // a lane's 32 signs of a chunk must be one Philox word
+  if ((K & 15) || !aligned16(x)) return MPQ_ERR_SHAPE;  // a lane's 16 signs of a chunk must sit in one Philox word
   return run_hutchinson(x, M, K, nullptr, seed, stream_id, P, quad_out, reinterpret_cast<float*>(ws),
                         (hipStream_t)stream);
 }

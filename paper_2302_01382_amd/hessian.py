@@ -23,7 +23,7 @@ def trace_linear_mse(x, probes: int = 32, seed: int = 0, stream_id: int = 0, ws:
     sign vectors.  x: device fp32 [M x K] (the layer's input activations; pass the weight matrix
     [N x K] for the trace with respect to the input).  Returns (estimate, standard error)."""
     M, K = x.shape
-    if K % 32 == 0 and x.data_ptr() % 16 == 0:   # the probes are drawn inside the kernel
+    if K % 16 == 0 and x.data_ptr() % 16 == 0:   # the probes are drawn inside the kernel
         q = mpq.hutchinson_quad_signs(x, seed, stream_id, probes, ws=ws).cpu().numpy()
     else:
         v = mpq.rademacher(seed, stream_id, probes, K, device=x.device)

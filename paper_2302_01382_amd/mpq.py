@@ -314,7 +314,7 @@ def hutchinson_quad(x, v, out=None, ws: Workspace = None):
 
 def hutchinson_quad_signs(x, seed: int, stream_id: int, probes: int, out=None, ws: Workspace = None):
     """hutchinson_quad for the sign probes rademacher(seed, stream_id, probes, K) would store, drawn
-    inside the kernel (K % 32 == 0, x 16-byte aligned)."""
+    inside the kernel (K % 16 == 0, x 16-byte aligned)."""
     torch = _torch()
     x = _dev2d(x, torch.float32)
     M, K = x.shape

@@ -228,7 +228,7 @@ def test_hutchinson_validation_and_workspace_query():
     assert f(FAKE16, 16384, 1024, FAKE16, 32, FAKE16, FAKE16, need - 4, None) == mpq.ERR_WORKSPACE
     g = L.mpq_hutchinson_quad_signs
     assert g(None, 64, 64, 1, 2, 32, FAKE16, FAKE16, need, None) == mpq.ERR_NULL
-    assert g(FAKE16, 64, 72, 1, 2, 32, FAKE16, FAKE16, need, None) == mpq.ERR_SHAPE       # K not a multiple of 32
+    assert g(FAKE16, 64, 72, 1, 2, 32, FAKE16, FAKE16, need, None) == mpq.ERR_SHAPE       # K not a multiple of 16
     assert g(C.c_void_p(0x10004), 64, 64, 1, 2, 32, FAKE16, FAKE16, need, None) == mpq.ERR_SHAPE   # x not 16-byte aligned
     assert g(FAKE16, 16384, 1024, 1, 2, 32, FAKE16, FAKE16, need - 4, None) == mpq.ERR_WORKSPACE
 

@@ -135,7 +135,7 @@ def test_gpu_rademacher_bit_exact(shape):
 
 @pytest.mark.gpu
 @pytest.mark.parametrize("mkp", [(64, 256, 32), (33, 31, 5), (1, 4, 1), (1000, 100, 40), (300, 70, 130), (4100, 1024, 64),
-                                 (2085, 2048, 96), (515, 36, 257), (40000, 64, 32), (100, 96, 70), (37, 32, 3), (200, 1056, 33), (100, 48, 5)])
+                                 (2085, 2048, 96), (515, 36, 257), (40000, 64, 32), (100, 96, 70), (37, 16, 3), (200, 1008, 33), (100, 48, 5), (64, 40, 8)])
 def test_gpu_hutchinson_quad_matches_the_oracle(mkp):
     from paper_2302_01382_amd import mpq
     M, K, P = mkp
@@ -150,7 +150,7 @@ def test_gpu_hutchinson_quad_matches_the_oracle(mkp):
     np.testing.assert_allclose(mpq.hutchinson_quad(dev(x), dev(g)).cpu().numpy(), oracle.hutchinson_quad(x, g), rtol=1e-4)
     # the sign probes drawn inside the kernel: the same bits as the stored matrix (k is summed in
     # another order, so the fp32 sums agree to rounding, not bit for bit)
-    if K % 32 == 0:
+    if K % 16 == 0:
         a = mpq.hutchinson_quad_signs(dev(x), 21, 0, P).cpu().numpy()
         np.testing.assert_allclose(a, want, rtol=1e-4, atol=0)
         np.testing.assert_allclose(a, mpq.hutchinson_quad(dev(x), mpq.rademacher(21, 0, P, K)).cpu().numpy(), rtol=2e-5)
