@@ -13,8 +13,9 @@ conv-as-GEMM stack (8 layers at batch 32).  Per layer a step runs, through the C
 Other workloads (the parity-test configurations, measured with the same machinery):
     cfg3  BERT-base encoder linears at M = 12288, same per-layer path, per-tensor scales
     cfg4  sensitivity sweep over the 96 BERT-large weight tensors: absmax + quant_error per tensor
-          and per output channel, noise at every b = 2..8 from one call per tensor
-          (cfg4-unfused: one call per granularity and per noise level)
+          and per output channel, noise at every b = 2..8 from one call per tensor; the tensors are
+          independent and are dealt to 4 streams (cfg4-1stream: one after the other;
+          cfg4-unfused: one call per granularity and per noise level, one stream)
     cfg5  64 candidate bit configurations of a BERT-large FFN block at M = 16384, back to back;
           GELU and the calibration of its output in the first GEMM's epilogue, the output score in
           the second's
@@ -323,7 +324,7 @@ def workload_layers(torch, P, workloads, which):
 
 # ------------------------------------------------------------------------------------------------
 # configuration 4: sensitivity sweep over the BERT-large weight set
-def workload_cfg4(torch, P, workloads, fused):
+def workload_cfg4(torch, P, workloads, fused, n_streams=1):
     tensors = [torch.from_numpy(w).cuda() for _, w in workloads.cfg4_tensors()]
     dev = tensors[0].device
     f32, f64 = torch.float32, torch.float64
@@ -332,13 +333,32 @@ def workload_cfg4(torch, P, workloads, fused):
     sse_t = [torch.empty((1, 7), dtype=f64, device=dev) for _ in tensors]
     sse_r = [torch.empty((t.shape[0], 7), dtype=f64, device=dev) for t in tensors]
     # one output buffer per shape: a plane per bit-width when the seven noise levels come from one call
-    noisy = {tuple(t.shape): torch.empty((7 if fused else 1,) + tuple(t.shape), dtype=f32, device=dev)
-             for t in tensors}
-    ws = P.Workspace()
-    ws.get(1 << 22)
+    # Tensors are independent: they are dealt round-robin to n_streams streams (each with its own
+    # workspace and noise buffers), so that the launch ramp of one small kernel overlaps the body
+    # of another.
+    noisy_s = [{tuple(t.shape): torch.empty((7 if fused else 1,) + tuple(t.shape), dtype=f32, device=dev)
+                for t in tensors} for _ in range(n_streams)]
+    ws_s = [P.Workspace() for _ in range(n_streams)]
+    for w in ws_s:
+        w.get(1 << 22)
+    extra = [torch.cuda.Stream() for _ in range(n_streams - 1)]   # default priority
 
     def step(rec):
+        # kernel-level timing (events around calls) is taken with the tensors in sequence, so that
+        # a call's duration is its own and not that of whatever shares the chip with it
+        lanes = 1 if isinstance(rec, EventRec) else n_streams
+        main = torch.cuda.current_stream()
+        for st in extra[:lanes - 1]:
+            st.wait_stream(main)
         for i, t in enumerate(tensors):
+            lane = i % lanes
+            with torch.cuda.stream(main if lane == 0 else extra[lane - 1]):
+                one_tensor(rec, i, t, ws_s[lane], noisy_s[lane])
+        for st in extra[:lanes - 1]:
+            main.wait_stream(st)
+
+    def one_tensor(rec, i, t, ws, noisy):
+        if True:
             n = t.numel()
             if fused:   # the tensor's maximum is the maximum of its row maxima: one read of the tensor
                 with rec("absmax", 4 * n):
@@ -685,9 +705,11 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", choices=["cfg2", "cfg3", "cfg4", "cfg4-unfused", "cfg5", "cfg5-twopass", "cfg5-unfused", "search", "latency", "hutchinson"], default="cfg2")
+    ap.add_argument("--workload", choices=["cfg2", "cfg3", "cfg4", "cfg4-1stream", "cfg4-unfused", "cfg5", "cfg5-twopass", "cfg5-unfused", "search", "latency", "hutchinson"], default="cfg2")
     ap.add_argument("--cpu-sample-rows", type=int, default=2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--streams", type=int, default=4,
+                    help="cfg4: streams the independent tensors are dealt to (the box has 4 hardware queues per process)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain device copy of known size (225792 KiB) three times before the "
                          "warm-up: the reference that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -721,8 +743,9 @@ def main():
     if args.workload in ("cfg2", "cfg3"):
         step, snapshot, nbytes, ops, label, layers = workload_layers(torch, mpq, workloads, args.workload)
         traffic = TRAFFIC_KIB_PER_LAUNCH_CFG2 if args.workload == "cfg2" else None
-    elif args.workload in ("cfg4", "cfg4-unfused"):
-        step, snapshot, nbytes, ops, label = workload_cfg4(torch, mpq, workloads, args.workload == "cfg4")
+    elif args.workload in ("cfg4", "cfg4-unfused", "cfg4-1stream"):
+        step, snapshot, nbytes, ops, label = workload_cfg4(torch, mpq, workloads, args.workload != "cfg4-unfused",
+                                                           args.streams if args.workload == "cfg4" else 1)
     else:
         step, snapshot, nbytes, ops, label, ncand = workload_cfg5(torch, mpq, workloads, {"cfg5": "onepass", "cfg5-twopass": "twopass", "cfg5-unfused": "unfused"}[args.workload])
         extra["candidates_per_step"] = ncand
