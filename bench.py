@@ -538,25 +538,28 @@ def cpu_baseline(workloads, sample_rows):
 def run_search(torch, mpq, workloads, args):
     """The loop the hot path exists for: Alg. 2 (greedy) and Alg. 1 (bisection) over a 24-layer
     stack of 1024 x 1024 layers at M = 4096, every evaluation a chain of libmpq launches ending in
-    one read-back of the score.  Reports evaluations per second, eager and with one HIP graph per
-    (layer, width)."""
+    one read-back of the score.  Reports evaluations per second with the evaluation issued as one
+    native call (mpq_stack_evaluate), call by call from Python, and as one HIP graph per (layer,
+    width)."""
     from paper_2302_01382_amd.stack import QuantStack
     layers, width, rows, bits, target = 24, 1024, 4096, [8, 4, 2], 0.9
     x, weights = workloads.search_stack(seed=6, layers=layers, width=width, rows=rows)
     dx, dws = torch.from_numpy(x).cuda(), [torch.from_numpy(w).cuda() for w in weights]
     res = {}
-    for mode, graphs in (("eager", False), ("hip_graph_per_layer_and_width", True)):
+    for mode, graphs in (("one_native_call", False), ("python_calls", False),
+                         ("python_calls_hip_graph_per_layer_and_width", True)):
         st = QuantStack(dx, dws, bits, 8, use_graphs=graphs)
+        ev = st.evaluate if mode == "one_native_call" else st.evaluate_by_calls
         order = st.order_by(st.qe_sensitivity(2))
         for b in bits:                       # warm-up: every (layer, width) pair once
-            st.evaluate([b] * layers)
+            ev([b] * layers)
         torch.cuda.synchronize()
         st.evaluations = 0
         t0 = time.perf_counter()
-        cfg_g, ev_g = st.greedy(order, target)
+        cfg_g, ev_g = st.greedy(order, target, ev)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-        cfg_b, ev_b = st.bisection(order, target)
+        cfg_b, ev_b = st.bisection(order, target, evaluate=ev)
         torch.cuda.synchronize()
         t2 = time.perf_counter()
         res[mode] = {"greedy": {"evaluations": ev_g, "seconds": t1 - t0, "evaluations_per_s": ev_g / (t1 - t0),
@@ -571,7 +574,7 @@ def run_search(torch, mpq, workloads, args):
             cfg = res[mode][alg].pop("config")
             res[mode][alg]["estimated_relative_latency"] = round(table.relative(shapes, cfg), 4)
             res[mode][alg]["relative_footprint"] = lat.relative_footprint(shapes, cfg)
-    best = res["hip_graph_per_layer_and_width"]["greedy"]
+    best = res["one_native_call"]["greedy"]
     ops_per_eval = 2.0 * rows * width * width * layers
     out = {
         "metric": "configuration-search evaluations/s (Alg. 2 greedy; each evaluation = the whole quantized stack)",

@@ -239,6 +239,34 @@ int mpq_scale_grad(const float* x, int64_t rows, int64_t cols, int gran, const f
 int mpq_scale_sgd_step(float* inv, float* scale, const double* dinv, const double* dscale,
                        int64_t count, double lr, void* stream);
 
+/* ---- "Evaluate f(x, lw) and save accuracy a" for a whole stack of layers in one call ------------
+ * The model f is n_layers linear layers with an activation between them.  Layer l has weights
+ * [N_l x K_l] (K_{l+1} = N_l) quantized beforehand at each of its n_widths candidate widths; an
+ * evaluation picks one width per layer (width_index[l], host array) and enqueues, per layer,
+ *   l > 0:  mpq_fake_quant(h_{l-1} -> a_codes_l, absmax a_absmax[l], act_bits), per tensor, with
+ *           the step size mpq_scale_from_absmax(a_absmax[l]) written to a_scale[l] by the same kernel,
+ *   l < n_layers - 1:  mpq_qgemm_act(..., act, h_l, running maximum into a_absmax[l + 1]),
+ *   last layer:        mpq_qgemm_score(..., y_ref) -> sse_out[0],
+ * i.e. the results of exactly those calls, in two launches per layer, issued from native code.
+ * a_absmax[1..] is cleared first (one small kernel).
+ * The caller provides layer 0's a_codes, a_absmax[0] and a_scale[0] (the model's input does not
+ * depend on the configuration).  mpq_stack_layer holds HOST arrays of DEVICE pointers.
+ * Errors: as the calls above; every argument is checked before the first launch. */
+typedef struct mpq_stack_layer {
+  int64_t N, K;                 /* weights [N x K] */
+  int n_widths;                 /* candidate widths of this layer */
+  const void* const* w_q;       /* [n_widths] device: int8 codes [N x K] or packed nibbles [N x K/2] */
+  const float* const* w_scale;  /* [n_widths] device: step sizes, [1] or [N] by w_gran */
+  const int* w_storage_bits;    /* [n_widths] host: 8 or 4 */
+  int8_t* a_codes;              /* device [M x K]: the layer's quantized input */
+  float* h;                     /* device [M x N] fp32: the layer's activated output; NULL for the last layer */
+} mpq_stack_layer;
+size_t mpq_stack_evaluate_workspace_bytes(const mpq_stack_layer* layers, int n_layers, int64_t M);
+int mpq_stack_evaluate(const mpq_stack_layer* layers, int n_layers, int64_t M, const int* width_index,
+                       int act_bits, int act, int w_gran, float* a_absmax /* device [n_layers] */,
+                       float* a_scale /* device [n_layers] */, const float* y_ref, double* sse_out,
+                       void* ws, size_t ws_bytes, void* stream);
+
 /* ---- Alg. 1 (bisection search) and Alg. 2 (greedy search): host code ---------------------------
  * Both decide which per-layer bit configuration to evaluate next and return the final one; they
  * launch nothing themselves.  All pointers here are HOST pointers.

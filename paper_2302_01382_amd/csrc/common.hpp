@@ -25,6 +25,10 @@ inline int launch_status() {
   return MPQ_OK;
 }
 
+// defined in fake_quant.hip: mpq_fake_quant plus the step size as an output of the same kernel
+int fake_quant_launch(const float* x, int64_t rows, int64_t cols, int gran, const float* absmax, int bits,
+                      float* y_out, int8_t* codes_out, uint8_t* packed4_out, float* step_out, void* stream);
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 inline bool mul_overflows(int64_t a, int64_t b) {

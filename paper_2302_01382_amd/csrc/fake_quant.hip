@@ -53,9 +53,10 @@ __device__ __forceinline__ void emit4(const float4 v, const QConst& c, int64_t i
 __global__ __launch_bounds__(kBlock) void fq_flat(const float* __restrict__ x, int64_t n,
                                                   const float* __restrict__ absmax, int bits,
                                                   float* __restrict__ y, int8_t* __restrict__ codes,
-                                                  uint8_t* __restrict__ packed) {
+                                                  uint8_t* __restrict__ packed, float* __restrict__ step_out) {
   const QConst c = make_qconst(absmax[0], bits);
   const int64_t tid = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (step_out && tid == 0) step_out[0] = c.scale;  // the step size the codes dequantize with
   const int64_t n4 = n >> 2;
   for_each_vec4_tiled(reinterpret_cast<const float4*>(x), n4,
                       [&](const float4 v, int64_t i) { emit4(v, c, i, y, codes, packed); });
@@ -122,9 +123,10 @@ __global__ __launch_bounds__(kBlock) void fq_generic(const float* __restrict__ x
                                                      int64_t cols, int gran,
                                                      const float* __restrict__ absmax, int bits,
                                                      float* __restrict__ y, int8_t* __restrict__ codes,
-                                                     uint8_t* __restrict__ packed) {
+                                                     uint8_t* __restrict__ packed, float* __restrict__ step_out) {
   const int64_t n = rows * cols;
   const int64_t npairs = (n + 1) >> 1;
+  if (step_out && blockIdx.x == 0 && threadIdx.x == 0) step_out[0] = make_qconst(absmax[0], bits).scale;  // per tensor only
   for (int64_t p = (int64_t)blockIdx.x * kBlock + threadIdx.x; p < npairs; p += (int64_t)gridDim.x * kBlock) {
     unsigned nib = 0;
     for (int e = 0; e < 2; ++e) {
@@ -142,14 +144,12 @@ __global__ __launch_bounds__(kBlock) void fq_generic(const float* __restrict__ x
   }
 }
 
-}  // namespace mpq
-
-using namespace mpq;
-
-extern "C" int mpq_fake_quant(const float* x, int64_t rows, int64_t cols, int gran,
-                              const float* absmax, int bits, float* y_out, int8_t* codes_out,
-                              uint8_t* packed4_out, void* stream) {
+// mpq_fake_quant with one more output: for per-tensor granularity the kernel also leaves the step
+// size scale_b in step_out[0] (what mpq_scale_from_absmax would compute in a launch of its own).
+int fake_quant_launch(const float* x, int64_t rows, int64_t cols, int gran, const float* absmax, int bits,
+                      float* y_out, int8_t* codes_out, uint8_t* packed4_out, float* step_out, void* stream) {
   if (!x || !absmax) return MPQ_ERR_NULL;
+  if (step_out && gran != MPQ_PER_TENSOR) return MPQ_ERR_GRAN;
   if (!y_out && !codes_out && !packed4_out) return MPQ_ERR_NULL;
   if (rows <= 0 || cols <= 0 || mul_overflows(rows, cols)) return MPQ_ERR_SHAPE;
   if (gran < MPQ_PER_TENSOR || gran > MPQ_PER_COL) return MPQ_ERR_GRAN;
@@ -162,7 +162,7 @@ extern "C" int mpq_fake_quant(const float* x, int64_t rows, int64_t cols, int gr
                       (!codes_out || (reinterpret_cast<uintptr_t>(codes_out) & 3u) == 0) &&
                       (!packed4_out || (reinterpret_cast<uintptr_t>(packed4_out) & 1u) == 0);
   if (vec_ok && gran == MPQ_PER_TENSOR) {
-    fq_flat<<<flat_grid(n >> 2, kBlock * kTileVec), kBlock, 0, st>>>(x, n, absmax, bits, y_out, codes_out, packed4_out);
+    fq_flat<<<flat_grid(n >> 2, kBlock * kTileVec), kBlock, 0, st>>>(x, n, absmax, bits, y_out, codes_out, packed4_out, step_out);
   } else if (vec_ok && gran == MPQ_PER_ROW && (cols & 3) == 0) {
     const int64_t nseg = (cols + kSeg - 1) / kSeg;
     const int64_t blocks = (rows * nseg + kBlock / kWave - 1) / (kBlock / kWave);
@@ -178,7 +178,17 @@ extern "C" int mpq_fake_quant(const float* x, int64_t rows, int64_t cols, int gr
     if (gy > 65535) gy = 65535;
     fq_cols<<<dim3((unsigned)gx, (unsigned)gy), kBlock, 0, st>>>(x, rows, cols, absmax, bits, y_out, codes_out, packed4_out);
   } else {
-    fq_generic<<<flat_grid((n + 1) >> 1, kBlock * 4), kBlock, 0, st>>>(x, rows, cols, gran, absmax, bits, y_out, codes_out, packed4_out);
+    fq_generic<<<flat_grid((n + 1) >> 1, kBlock * 4), kBlock, 0, st>>>(x, rows, cols, gran, absmax, bits, y_out, codes_out, packed4_out, step_out);
   }
   return launch_status();
+}
+
+}  // namespace mpq
+
+using namespace mpq;
+
+extern "C" int mpq_fake_quant(const float* x, int64_t rows, int64_t cols, int gran,
+                              const float* absmax, int bits, float* y_out, int8_t* codes_out,
+                              uint8_t* packed4_out, void* stream) {
+  return fake_quant_launch(x, rows, cols, gran, absmax, bits, y_out, codes_out, packed4_out, nullptr, stream);
 }

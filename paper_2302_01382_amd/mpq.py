@@ -24,7 +24,7 @@ EXPORTS = [
     "mpq_sse_pair_workspace_bytes", "mpq_sse_pair", "mpq_qgemm_score_workspace_bytes", "mpq_qgemm_score",
     "mpq_search_bisection", "mpq_search_greedy", "mpq_noise_inject_sweep",
     "mpq_fake_quant_scales", "mpq_scale_grad_workspace_bytes", "mpq_scale_grad", "mpq_scale_sgd_step", "mpq_qgemm_act", "mpq_qgemm_act_codes",
-    "mpq_rademacher", "mpq_hutchinson_quad_workspace_bytes", "mpq_hutchinson_quad", "mpq_hutchinson_quad_signs",
+    "mpq_stack_evaluate_workspace_bytes", "mpq_stack_evaluate", "mpq_rademacher", "mpq_hutchinson_quad_workspace_bytes", "mpq_hutchinson_quad", "mpq_hutchinson_quad_signs",
 ]
 
 ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
@@ -79,6 +79,9 @@ def lib():
         L.mpq_scale_sgd_step.argtypes = [vp, vp, vp, vp, i64, C.c_double, vp]
         L.mpq_qgemm_act.argtypes = [vp, vp, ci, i64, i64, i64, vp, vp, ci, ci, vp, vp, ci, vp]
         L.mpq_qgemm_act_codes.argtypes = [vp, vp, ci, i64, i64, i64, vp, vp, ci, ci, vp, ci, vp, vp]
+        L.mpq_stack_evaluate_workspace_bytes.argtypes = [vp, ci, i64]
+        L.mpq_stack_evaluate_workspace_bytes.restype = C.c_size_t
+        L.mpq_stack_evaluate.argtypes = [vp, ci, i64, vp, ci, ci, ci, vp, vp, vp, vp, vp, C.c_size_t, vp]
         L.mpq_rademacher.argtypes = [C.c_uint64, C.c_uint64, i64, i64, vp, vp]
         L.mpq_hutchinson_quad_workspace_bytes.argtypes = [i64, i64, i64]
         L.mpq_hutchinson_quad_workspace_bytes.restype = C.c_size_t
@@ -290,6 +293,60 @@ def rademacher(seed: int, stream_id: int, rows: int, cols: int, out=None, device
     _check(lib().mpq_rademacher(seed & (2 ** 64 - 1), stream_id & (2 ** 64 - 1), rows, cols, _ptr(out), _stream()),
            "mpq_rademacher")
     return out
+
+
+class StackLayer(C.Structure):
+    """mpq_stack_layer of include/mpq.h: host arrays of device pointers."""
+    _fields_ = [("N", C.c_int64), ("K", C.c_int64), ("n_widths", C.c_int),
+                ("w_q", C.POINTER(C.c_void_p)), ("w_scale", C.POINTER(C.c_void_p)),
+                ("w_storage_bits", C.POINTER(C.c_int)), ("a_codes", C.c_void_p), ("h", C.c_void_p)]
+
+
+class StackPlan:
+    """The argument block of mpq_stack_evaluate for a fixed stack, built once: per layer the weight
+    codes / step sizes / storage widths of every candidate width, the code buffer of its input and
+    its fp32 output.  Keeps the tensors alive."""
+
+    def __init__(self, M, layers, a_absmax, a_scale, y_ref, act_bits, act, w_gran):
+        """layers: list of dicts {N, K, w_q: [tensor], w_scale: [tensor], store: [int], a_codes: tensor,
+        h: tensor | None} in stack order."""
+        self.keep = (layers, a_absmax, a_scale, y_ref)
+        n = len(layers)
+        self.arr = (StackLayer * n)()
+        self._hold = []
+        for i, L in enumerate(layers):
+            nw = len(L["w_q"])
+            wq = (C.c_void_p * nw)(*[t.data_ptr() for t in L["w_q"]])
+            ws_ = (C.c_void_p * nw)(*[t.data_ptr() for t in L["w_scale"]])
+            st = (C.c_int * nw)(*[int(b) for b in L["store"]])
+            self._hold += [wq, ws_, st]
+            self.arr[i] = StackLayer(L["N"], L["K"], nw, C.cast(wq, C.POINTER(C.c_void_p)),
+                                     C.cast(ws_, C.POINTER(C.c_void_p)), C.cast(st, C.POINTER(C.c_int)),
+                                     L["a_codes"].data_ptr(), None if L["h"] is None else L["h"].data_ptr())
+        self.n, self.M = n, int(M)
+        self.a_absmax, self.a_scale, self.y_ref = a_absmax, a_scale, y_ref
+        self.act_bits, self.act, self.w_gran = int(act_bits), int(act), int(w_gran)
+        self.idx = (C.c_int * n)()
+        self.ws_bytes = int(lib().mpq_stack_evaluate_workspace_bytes(self.arr, n, self.M))
+
+    def evaluate(self, width_index, sse_out, ws: "Workspace" = None):
+        """Enqueues one evaluation with layer l at its candidate width number width_index[l]."""
+        for i, w in enumerate(width_index):
+            self.idx[i] = int(w)
+        wp, wn = (ws or _default_ws).get(self.ws_bytes)
+        _check(lib().mpq_stack_evaluate(self.arr, self.n, self.M, self.idx, self.act_bits, self.act, self.w_gran,
+                                        _ptr(self.a_absmax), _ptr(self.a_scale), _ptr(self.y_ref), _ptr(sse_out),
+                                        wp, wn, _stream()), "mpq_stack_evaluate")
+        return sse_out
+
+
+def stack_evaluate_workspace_bytes(plan: "StackPlan") -> int:
+    return plan.ws_bytes
+
+
+def stack_evaluate(plan: "StackPlan", width_index, sse_out, ws: "Workspace" = None):
+    """One evaluation of a stack (see StackPlan): layer l at its candidate width number width_index[l]."""
+    return plan.evaluate(width_index, sse_out, ws)
 
 
 def hutchinson_quad_workspace_bytes(M, K, P) -> int:

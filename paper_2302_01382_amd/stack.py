@@ -22,9 +22,10 @@ class QuantStack:
                  w_gran: int = mpq.PER_ROW, use_graphs: bool = False):
         """x: fp32 device tensor [M, K_1]; weights: fp32 device tensors [N_l, K_l] with K_{l+1} = N_l;
         bit_widths: the widths (2..8) a layer may be given.
-        use_graphs: the launches of layer l at width b (calibrate, quantize, step size, GEMM, ReLU)
-        are captured into a HIP graph the first time that pair is evaluated and replayed from then
-        on, so an evaluation costs one launch per layer instead of six."""
+        use_graphs: in evaluate_by_calls, the launches of layer l at width b (quantize, step size,
+        GEMM + ReLU + calibration) are captured into a HIP graph the first time that pair is
+        evaluated and replayed from then on.  evaluate() itself issues everything from one native
+        call and needs no graphs."""
         import torch
         self.torch = torch
         self.x = x.contiguous()
@@ -59,8 +60,12 @@ class QuantStack:
                 per_b[b] = (codes if store == 8 else packed, mpq.scale_from_absmax(am, b), store)
             self.w_q.append(per_b)
         # buffers of one evaluation
-        self.a_absmax = [torch.empty(1, dtype=f32, device=dev) for _ in self.weights]
-        self.a_scale = [torch.empty(1, dtype=f32, device=dev) for _ in self.weights]
+        # one tensor for all layers' input maxima: the running maxima of layers 1.. are cleared by a
+        # single fill at the start of an evaluation instead of one small kernel in front of every GEMM
+        self.a_absmax_all = torch.zeros(len(self.weights), dtype=f32, device=dev)
+        self.a_absmax = [self.a_absmax_all[l:l + 1] for l in range(len(self.weights))]
+        self.a_scale_all = torch.empty(len(self.weights), dtype=f32, device=dev)
+        self.a_scale = [self.a_scale_all[l:l + 1] for l in range(len(self.weights))]
         self.a_codes = [torch.empty((M, w.shape[1]), dtype=torch.int8, device=dev) for w in self.weights]
         self.h = [torch.empty((M, w.shape[0]), dtype=f32, device=dev) for w in self.weights[:-1]]
         self.sse = torch.empty(1, dtype=torch.float64, device=dev)
@@ -71,12 +76,31 @@ class QuantStack:
         self.evaluations = 0
         self.use_graphs = use_graphs
         self.graphs = {}
+        # the whole evaluation as one native call (mpq_stack_evaluate): the argument block is built once
+        widths = self.bit_widths
+        self.width_number = {b: i for i, b in enumerate(widths)}
+        self.plan = mpq.StackPlan(
+            M, [{"N": w.shape[0], "K": w.shape[1], "w_q": [self.w_q[l][b][0] for b in widths],
+                 "w_scale": [self.w_q[l][b][1] for b in widths], "store": [self.w_q[l][b][2] for b in widths],
+                 "a_codes": self.a_codes[l], "h": self.h[l] if l + 1 < len(self.weights) else None}
+                for l, w in enumerate(self.weights)],
+            self.a_absmax_all, self.a_scale_all, self.y_ref, self.act_bits, mpq.ACT_RELU, w_gran)
 
     def __len__(self):
         return len(self.weights)
 
     def evaluate(self, bits: Sequence[int]) -> float:
-        """Accuracy 1 - SSE / ||Y_ref||^2 of the stack with layer l's weights at bits[l]."""
+        """Accuracy 1 - SSE / ||Y_ref||^2 of the stack with layer l's weights at bits[l]: one native
+        call enqueues every layer, then the one read-back of an evaluation."""
+        self.plan.evaluate([self.width_number[int(b)] for b in bits], self.sse, self.ws)
+        self.evaluations += 1
+        return 1.0 - float(self.sse.item()) / self.ref_norm2
+
+    def evaluate_by_calls(self, bits: Sequence[int]) -> float:
+        """The same evaluation issued call by call from Python (optionally as one HIP graph per
+        (layer, width)); kept as the reference the native call is checked against."""
+        if len(self.weights) > 1:
+            self.a_absmax_all[1:].zero_()   # a fill kernel; the epilogues below keep running maxima
         for l in range(len(self.weights)):
             b = int(bits[l])
             if not self.use_graphs:
@@ -106,7 +130,7 @@ class QuantStack:
         if l + 1 < len(self.weights):
             # ReLU and the max calibration of the next layer's input are taken in the epilogue
             P.qgemm_act(self.a_codes[l], wq, self.a_scale[l], sw, P.ACT_RELU, store, self.w_gran, y=self.h[l],
-                        absmax=self.a_absmax[l + 1])
+                        absmax=self.a_absmax[l + 1], accumulate=True)
         else:
             P.qgemm_score(self.a_codes[l], wq, self.a_scale[l], sw, self.y_ref, store, self.w_gran,
                           out=self.sse, ws=self.ws)
@@ -125,8 +149,9 @@ class QuantStack:
         """Layer ids in ascending order of sensitivity (ties: lower id first)."""
         return sorted(range(len(self.weights)), key=lambda l: (sensitivity[l], l))
 
-    def bisection(self, order, target, ensure_target=True):
-        return mpq.search_bisection(order, sorted(self.bit_widths, reverse=True), target, self.evaluate, ensure_target)
+    def bisection(self, order, target, ensure_target=True, evaluate=None):
+        return mpq.search_bisection(order, sorted(self.bit_widths, reverse=True), target, evaluate or self.evaluate,
+                                    ensure_target)
 
-    def greedy(self, order, target):
-        return mpq.search_greedy(order, sorted(self.bit_widths, reverse=True), target, self.evaluate)
+    def greedy(self, order, target, evaluate=None):
+        return mpq.search_greedy(order, sorted(self.bit_widths, reverse=True), target, evaluate or self.evaluate)

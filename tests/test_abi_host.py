@@ -234,6 +234,42 @@ def test_hutchinson_validation_and_workspace_query():
 
 
 @needs_no_gpu
+def test_stack_evaluate_validation():
+    L = mpq.lib()
+    f = L.mpq_stack_evaluate
+    nw = 2
+    wq = (C.c_void_p * nw)(0x10000, 0x20000)
+    wsc = (C.c_void_p * nw)(0x30000, 0x40000)
+    st = (C.c_int * nw)(8, 4)
+
+    def layer(N, K, h, store=st):
+        return mpq.StackLayer(N, K, nw, C.cast(wq, C.POINTER(C.c_void_p)), C.cast(wsc, C.POINTER(C.c_void_p)),
+                              C.cast(store, C.POINTER(C.c_int)), 0x50000, h)
+
+    arr = (mpq.StackLayer * 2)(layer(64, 32, 0x60000), layer(16, 64, None))
+    idx = (C.c_int * 2)(0, 1)
+    need = L.mpq_stack_evaluate_workspace_bytes(arr, 2, 128)
+    assert need == L.mpq_qgemm_score_workspace_bytes(128, 16, 64, 8) > 0
+    tail = (FAKE16, FAKE16, FAKE16, FAKE16, FAKE16, need, None)
+    assert f(None, 2, 128, idx, 8, 1, 0, *tail) == mpq.ERR_NULL
+    assert f(arr, 2, 128, None, 8, 1, 0, *tail) == mpq.ERR_NULL
+    assert f(arr, 0, 128, idx, 8, 1, 0, *tail) == mpq.ERR_SHAPE
+    assert f(arr, 2, 128, idx, 9, 1, 0, *tail) == mpq.ERR_BITS
+    assert f(arr, 2, 128, idx, 8, 7, 0, *tail) == mpq.ERR_SHAPE
+    assert f(arr, 2, 128, (C.c_int * 2)(0, 2), 8, 1, 0, *tail) == mpq.ERR_SHAPE          # no such candidate width
+    assert f(arr, 2, 128, idx, 8, 1, 0, FAKE16, FAKE16, FAKE16, FAKE16, FAKE16, need - 8, None) == mpq.ERR_WORKSPACE
+    assert f(arr, 2, 128, idx, 8, 1, 0, FAKE16, FAKE16, None, FAKE16, FAKE16, need, None) == mpq.ERR_NULL
+    broken = (mpq.StackLayer * 2)(layer(64, 32, 0x60000), layer(16, 48, None))            # 48 != 64: does not chain
+    assert f(broken, 2, 128, idx, 8, 1, 0, *tail) == mpq.ERR_SHAPE
+    no_h = (mpq.StackLayer * 2)(layer(64, 32, None), layer(16, 64, None))
+    assert f(no_h, 2, 128, idx, 8, 1, 0, *tail) == mpq.ERR_NULL
+    odd = (mpq.StackLayer * 1)(layer(16, 33, None))
+    assert f(odd, 1, 128, (C.c_int * 1)(1), 8, 1, 0, *tail) == mpq.ERR_SHAPE               # packed nibbles need even K
+    bad_store = (C.c_int * nw)(8, 6)
+    assert f((mpq.StackLayer * 1)(layer(16, 32, None, bad_store)), 1, 128, (C.c_int * 1)(1), 8, 1, 0, *tail) == mpq.ERR_BITS
+
+
+@needs_no_gpu
 def test_scale_adjust_validation():
     L = mpq.lib()
     assert L.mpq_scale_grad_workspace_bytes(64, 64, 0) > 0

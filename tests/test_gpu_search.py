@@ -135,7 +135,9 @@ def test_graph_replayed_evaluations_equal_eager_ones(stacks):
     r = np.random.Generator(np.random.PCG64(9))
     for _ in range(20):
         bits = [int(v) for v in r.choice(BITS, len(weights))]
-        assert graphed.evaluate(bits) == gpu.evaluate(bits)
+        # graph replays, eager calls from Python and the one native call: the same launches, the same bits
+        assert graphed.evaluate_by_calls(bits) == gpu.evaluate_by_calls(bits) == gpu.evaluate(bits)
     assert len(graphed.graphs) == len(weights) * len(BITS)
     order = list(range(len(weights)))
-    assert graphed.greedy(order, 0.9) == gpu.greedy(order, 0.9)
+    assert graphed.greedy(order, 0.9, graphed.evaluate_by_calls) == gpu.greedy(order, 0.9) == \
+        gpu.greedy(order, 0.9, gpu.evaluate_by_calls)
