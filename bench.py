@@ -7,7 +7,7 @@ conv-as-GEMM stack (8 layers at batch 32).  Per layer a step runs, through the C
     absmax(A) per tensor, absmax(W) per output channel            (calibration, Sec. 3.1)
     quant_error(A) and quant_error(W), b = 2..8 in one read each  (Eq. 2)
     noise_inject(W) at the layer's weight bit-width               (Eq. 3-5)
-    fake_quant(A) -> int8 codes, fake_quant(W) -> int8 / packed int4 codes, the two step sizes
+    fake_quant(A) -> int8 codes + step size, fake_quant(W) -> int8 / packed int4 codes, its step sizes
     qgemm -> fp32 Y                                               ("Evaluate f(x, w)")
     sse_pair(Y, Y_ref)                                            (candidate score)
 Other workloads (the parity-test configurations, measured with the same machinery):
@@ -268,18 +268,18 @@ def run_layer(P, L, ws_a, ws_w, rec, torch, side):
         P.calibrate_absmax(L.w, L.w_gran, out=L.am_w, ws=ws_w)
         P.quant_error(L.w, L.am_w, 2, 8, L.w_gran, out=L.sse_w, ws=ws_w)
         P.noise_inject(L.w, L.am_w, L.bits_w, LAMBDA, 2302, L.idx, L.w_gran, out=L.w_noisy)
-        if L.w_store == 4:
-            P.fake_quant(L.w, L.am_w, L.bits_w, L.w_gran, want_y=False, packed4=L.w_codes)
+        wq = {"packed4": L.w_codes} if L.w_store == 4 else {"codes": L.w_codes}
+        if L.w_gran == P.PER_TENSOR:   # the quantizer kernel also leaves the step size
+            P.fake_quant_step(L.w, L.am_w, L.bits_w, want_y=False, step=L.s_w, **wq)
         else:
-            P.fake_quant(L.w, L.am_w, L.bits_w, L.w_gran, want_y=False, codes=L.w_codes)
-        P.scale_from_absmax(L.am_w, L.bits_w, out=L.s_w)
+            P.fake_quant(L.w, L.am_w, L.bits_w, L.w_gran, want_y=False, **wq)
+            P.scale_from_absmax(L.am_w, L.bits_w, out=L.s_w)
     with rec("absmax", 4 * mk):
         P.calibrate_absmax(L.a, P.PER_TENSOR, out=L.am_a, ws=ws_a)
     with rec("quant_error", 4 * mk):
         P.quant_error(L.a, L.am_a, 2, 8, P.PER_TENSOR, out=L.sse_a, ws=ws_a)
     with rec("fake_quant", 5 * mk):
-        P.fake_quant(L.a, L.am_a, L.bits_a, P.PER_TENSOR, want_y=False, codes=L.a_codes)
-    P.scale_from_absmax(L.am_a, L.bits_a, out=L.s_a)
+        P.fake_quant_step(L.a, L.am_a, L.bits_a, want_y=False, codes=L.a_codes, step=L.s_a)
     main.wait_stream(side)
     with rec("qgemm", mk + wb + 4 * mn, L.ops()):
         P.qgemm(L.a_codes, L.w_codes, L.s_a, L.s_w, L.w_store, L.w_gran, y=L.y, ws=ws_a)
@@ -461,8 +461,9 @@ def workload_cfg5(torch, P, workloads, mode):
                     P.calibrate_absmax(h, out=am_h, ws=ws)
             if mode != "twopass":
                 with rec("fake_quant", 5 * h.numel()):
-                    P.fake_quant(h, am_h, ba2, want_y=False, codes=ch)
-            P.scale_from_absmax(am_h, ba2, out=s_h)
+                    P.fake_quant_step(h, am_h, ba2, want_y=False, codes=ch, step=s_h)
+            else:
+                P.scale_from_absmax(am_h, ba2, out=s_h)
             if fused:  # the score is taken in the epilogue: Y_ref is read, Y is never written
                 with rec("qgemm", M * N1 + N2 * N1 * st2 // 8 + 4 * M * N2, 2 * M * N2 * N1):
                     P.qgemm_score(ch, q2, s_h, s_w2[bw2], y_ref, st2, out=scores[c:c + 1], ws=ws)

@@ -87,6 +87,13 @@ int mpq_scale_from_absmax(const float* absmax, int64_t count, int bits, float* s
  * At least one output must be given.  No workspace. */
 int mpq_fake_quant(const float* x, int64_t rows, int64_t cols, int gran, const float* absmax,
                    int bits, float* y_out, int8_t* codes_out, uint8_t* packed4_out, void* stream);
+/* Per-tensor mpq_fake_quant that also leaves the step size scale_b = absmax / qmax_b in step_out[0]
+ * (device float[1], required): what mpq_scale_from_absmax(absmax, 1, bits) computes, without a
+ * launch of its own for one division.  Other arguments and errors as mpq_fake_quant. */
+int mpq_fake_quant_step(const float* x, int64_t rows, int64_t cols, const float* absmax, int bits,
+                        float* y_out, int8_t* codes_out, uint8_t* packed4_out, float* step_out,
+                        void* stream);
+
 
 /* ---- Sec. 3.2.1 Eq. 2: quantization-error sums for b = b_lo..b_hi in ONE read of x -----------
  * sse_out    double [nch x nb], channel-major, b ascending; nch = 1 | rows | cols, nb =

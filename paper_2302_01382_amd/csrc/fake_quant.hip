@@ -192,3 +192,11 @@ extern "C" int mpq_fake_quant(const float* x, int64_t rows, int64_t cols, int gr
                               uint8_t* packed4_out, void* stream) {
   return fake_quant_launch(x, rows, cols, gran, absmax, bits, y_out, codes_out, packed4_out, nullptr, stream);
 }
+
+extern "C" int mpq_fake_quant_step(const float* x, int64_t rows, int64_t cols, const float* absmax, int bits,
+                                   float* y_out, int8_t* codes_out, uint8_t* packed4_out, float* step_out,
+                                   void* stream) {
+  if (!step_out) return MPQ_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(step_out) & 3u) return MPQ_ERR_ALIGN;
+  return fake_quant_launch(x, rows, cols, MPQ_PER_TENSOR, absmax, bits, y_out, codes_out, packed4_out, step_out, stream);
+}

@@ -24,7 +24,7 @@ EXPORTS = [
     "mpq_sse_pair_workspace_bytes", "mpq_sse_pair", "mpq_qgemm_score_workspace_bytes", "mpq_qgemm_score",
     "mpq_search_bisection", "mpq_search_greedy", "mpq_noise_inject_sweep",
     "mpq_fake_quant_scales", "mpq_scale_grad_workspace_bytes", "mpq_scale_grad", "mpq_scale_sgd_step", "mpq_qgemm_act", "mpq_qgemm_act_codes",
-    "mpq_stack_evaluate_workspace_bytes", "mpq_stack_evaluate", "mpq_rademacher", "mpq_hutchinson_quad_workspace_bytes", "mpq_hutchinson_quad", "mpq_hutchinson_quad_signs",
+    "mpq_fake_quant_step", "mpq_stack_evaluate_workspace_bytes", "mpq_stack_evaluate", "mpq_rademacher", "mpq_hutchinson_quad_workspace_bytes", "mpq_hutchinson_quad", "mpq_hutchinson_quad_signs",
 ]
 
 ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
@@ -79,6 +79,7 @@ def lib():
         L.mpq_scale_sgd_step.argtypes = [vp, vp, vp, vp, i64, C.c_double, vp]
         L.mpq_qgemm_act.argtypes = [vp, vp, ci, i64, i64, i64, vp, vp, ci, ci, vp, vp, ci, vp]
         L.mpq_qgemm_act_codes.argtypes = [vp, vp, ci, i64, i64, i64, vp, vp, ci, ci, vp, ci, vp, vp]
+        L.mpq_fake_quant_step.argtypes = [vp, i64, i64, vp, ci, vp, vp, vp, vp, vp]
         L.mpq_stack_evaluate_workspace_bytes.argtypes = [vp, ci, i64]
         L.mpq_stack_evaluate_workspace_bytes.restype = C.c_size_t
         L.mpq_stack_evaluate.argtypes = [vp, ci, i64, vp, ci, ci, ci, vp, vp, vp, vp, vp, C.c_size_t, vp]
@@ -198,6 +199,26 @@ def fake_quant(x, absmax, bits, gran=PER_TENSOR, want_y=True, want_codes=False, 
     _check(lib().mpq_fake_quant(_ptr(x), rows, cols, gran, _ptr(absmax), bits, _ptr(y), _ptr(codes),
                                 _ptr(packed4), _stream()), "mpq_fake_quant")
     return y, codes, packed4
+
+
+def fake_quant_step(x, absmax, bits, want_y=True, want_codes=False, want_packed4=False, y=None, codes=None,
+                    packed4=None, step=None):
+    """Per-tensor fake_quant whose kernel also leaves the step size absmax / qmax_b.
+    Returns (y | None, codes | None, packed4 | None, step float32[1])."""
+    torch = _torch()
+    x = _dev2d(x, torch.float32)
+    rows, cols = x.shape
+    if want_y and y is None:
+        y = torch.empty_like(x)
+    if want_codes and codes is None:
+        codes = torch.empty((rows, cols), dtype=torch.int8, device=x.device)
+    if want_packed4 and packed4 is None:
+        packed4 = torch.empty((rows, cols // 2), dtype=torch.uint8, device=x.device)
+    if step is None:
+        step = torch.empty(1, dtype=torch.float32, device=x.device)
+    _check(lib().mpq_fake_quant_step(_ptr(x), rows, cols, _ptr(absmax), bits, _ptr(y), _ptr(codes), _ptr(packed4),
+                                     _ptr(step), _stream()), "mpq_fake_quant_step")
+    return y, codes, packed4, step
 
 
 def quant_error_workspace_bytes(rows, cols, gran=PER_TENSOR, b_lo=2, b_hi=8) -> int:

@@ -94,6 +94,18 @@ def test_fake_quant_validation():
 
 
 @needs_no_gpu
+def test_fake_quant_step_validation():
+    f = mpq.lib().mpq_fake_quant_step
+    assert f(FAKE, 4, 4, FAKE, 8, FAKE, None, None, None, None) == mpq.ERR_NULL           # no step_out
+    assert f(FAKE, 4, 4, FAKE, 8, FAKE, None, None, C.c_void_p(0x1002), None) == mpq.ERR_ALIGN
+    assert f(None, 4, 4, FAKE, 8, FAKE, None, None, FAKE, None) == mpq.ERR_NULL
+    assert f(FAKE, 4, 4, FAKE, 8, None, None, None, FAKE, None) == mpq.ERR_NULL           # no output
+    assert f(FAKE, 4, 4, FAKE, 9, FAKE, None, None, FAKE, None) == mpq.ERR_BITS
+    assert f(FAKE, 0, 4, FAKE, 8, FAKE, None, None, FAKE, None) == mpq.ERR_SHAPE
+    assert f(FAKE, 4, 3, FAKE, 4, None, None, FAKE, FAKE, None) == mpq.ERR_SHAPE          # packed nibbles need even cols
+
+
+@needs_no_gpu
 def test_quant_error_validation_and_workspace_query():
     L = mpq.lib()
     f = L.mpq_quant_error

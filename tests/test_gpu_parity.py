@@ -96,6 +96,27 @@ def test_fake_quant_codes_bit_exact_all_bits(shape, gran):
                 np.testing.assert_array_equal(host(p), p_o)
 
 
+@pytest.mark.parametrize("shape", [(1, 1), (7, 13), (64, 256), (300, 1030)])
+def test_fake_quant_step_is_fake_quant_plus_the_step_size(shape):
+    x = data(shape, 33)
+    am_o = oracle.absmax(x)
+    for mk in (dev, dev_misaligned):
+        dx = mk(x)
+        am = mpq.calibrate_absmax(dx)
+        for bits in (2, 4, 8):
+            y, codes, _, step = mpq.fake_quant_step(dx, am, bits, want_codes=True)
+            y_o, c_o, _ = oracle.fake_quant(x, am_o, bits)
+            np.testing.assert_array_equal(host(codes), c_o)
+            np.testing.assert_allclose(host(y), y_o, rtol=RTOL_Y, atol=0)
+            np.testing.assert_array_equal(host(step), oracle.scale_from_absmax(am_o, bits))
+            np.testing.assert_array_equal(host(step), host(mpq.scale_from_absmax(am, bits)))
+    if shape[1] % 2 == 0:
+        _, _, packed, step = mpq.fake_quant_step(dev(x), dev(am_o), 4, want_y=False, want_packed4=True)
+        _, _, p_o = oracle.fake_quant(x, am_o, 4, want_packed4=True)
+        np.testing.assert_array_equal(host(packed), p_o)
+        np.testing.assert_array_equal(host(step), oracle.scale_from_absmax(am_o, 4))
+
+
 def test_fake_quant_saturation_zero_channels_and_single_outputs():
     x = data((130, 516), 5)
     for gran in GRANS:
