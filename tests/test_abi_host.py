@@ -40,6 +40,19 @@ def test_library_exports_every_declared_symbol():
     assert sorted(mpq.EXPORTS) == names
 
 
+def test_header_is_plain_c():
+    """The boundary is a C ABI: the header must compile as C99 (and as C++) with warnings on."""
+    import shutil
+    import subprocess
+    hdr = os.path.join(ROOT, "include", "mpq.h")
+    for cc, std, lang in (("gcc", "-std=c99", "c"), ("g++", "-std=c++17", "c++")):
+        if shutil.which(cc) is None:
+            pytest.skip("no host compiler")
+        r = subprocess.run([cc, std, "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", lang, hdr],
+                           capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
+
+
 def test_binding_module_has_the_same_names():
     for n in declared_functions():
         short = n[len("mpq_"):]
