@@ -358,26 +358,25 @@ def workload_cfg4(torch, P, workloads, fused, n_streams=1):
             main.wait_stream(st)
 
     def one_tensor(rec, i, t, ws, noisy):
-        if True:
-            n = t.numel()
-            if fused:   # the tensor's maximum is the maximum of its row maxima: one read of the tensor
-                with rec("absmax", 4 * n):
-                    P.calibrate_absmax(t, P.PER_ROW, out=am_r[i])
-                    P.calibrate_absmax(am_r[i].view(1, -1), P.PER_TENSOR, out=am_t[i], ws=ws)
-            else:
-                with rec("absmax", 8 * n):
-                    P.calibrate_absmax(t, P.PER_TENSOR, out=am_t[i], ws=ws)
-                    P.calibrate_absmax(t, P.PER_ROW, out=am_r[i])
-            with rec("quant_error", 8 * n):
-                P.quant_error(t, am_t[i], 2, 8, P.PER_TENSOR, out=sse_t[i], ws=ws)
-                P.quant_error(t, am_r[i], 2, 8, P.PER_ROW, out=sse_r[i], ws=ws)
-            if fused:   # z does not depend on b: drawn once, seven outputs
-                with rec("noise_inject", (4 + 7 * 4) * n):
-                    P.noise_inject_sweep(t, am_r[i], 2, 8, LAMBDA, 2302, i, P.PER_ROW, out=noisy[tuple(t.shape)])
-            else:
-                with rec("noise_inject", 7 * 8 * n):
-                    for b in range(2, 9):
-                        P.noise_inject(t, am_r[i], b, LAMBDA, 2302, i, P.PER_ROW, out=noisy[tuple(t.shape)][0])
+        n = t.numel()
+        if fused:   # the tensor's maximum is the maximum of its row maxima: one read of the tensor
+            with rec("absmax", 4 * n):
+                P.calibrate_absmax(t, P.PER_ROW, out=am_r[i])
+                P.calibrate_absmax(am_r[i].view(1, -1), P.PER_TENSOR, out=am_t[i], ws=ws)
+        else:
+            with rec("absmax", 8 * n):
+                P.calibrate_absmax(t, P.PER_TENSOR, out=am_t[i], ws=ws)
+                P.calibrate_absmax(t, P.PER_ROW, out=am_r[i])
+        with rec("quant_error", 8 * n):
+            P.quant_error(t, am_t[i], 2, 8, P.PER_TENSOR, out=sse_t[i], ws=ws)
+            P.quant_error(t, am_r[i], 2, 8, P.PER_ROW, out=sse_r[i], ws=ws)
+        if fused:   # z does not depend on b: drawn once, seven outputs
+            with rec("noise_inject", (4 + 7 * 4) * n):
+                P.noise_inject_sweep(t, am_r[i], 2, 8, LAMBDA, 2302, i, P.PER_ROW, out=noisy[tuple(t.shape)])
+        else:
+            with rec("noise_inject", 7 * 8 * n):
+                for b in range(2, 9):
+                    P.noise_inject(t, am_r[i], b, LAMBDA, 2302, i, P.PER_ROW, out=noisy[tuple(t.shape)][0])
 
     def snapshot():
         return [s.clone() for s in sse_t] + [s.clone() for s in sse_r[:8]]

@@ -224,7 +224,7 @@ def test_noise_sweep_planes_equal_single_calls_bit_exact(shape, gran):
             np.testing.assert_array_equal(got, want)
         # planes further apart than one tensor (and not a multiple of 4 elements apart)
         buf = t.full((nb, x.size + 3), -1.0, dtype=t.float32, device="cuda")
-        out = buf[:, :x.size].view(nb, *x.shape) if False else buf.as_strided((nb,) + x.shape, (x.size + 3, x.shape[1], 1))
+        out = buf.as_strided((nb,) + x.shape, (x.size + 3, x.shape[1], 1))
         mpq.noise_inject_sweep(dev(x), dev(am), b_lo, b_hi, lam, seed, sid, gran, out=out)
         np.testing.assert_array_equal(host(out), want)
         assert (host(buf)[:, x.size:] == -1.0).all()   # the gaps between planes are left alone
@@ -413,7 +413,7 @@ def test_qgemm_act_matches_the_composition(mnk, wbits, act):
     assert host(am)[0] == np.float32(1e30)
     y, none = mpq.qgemm_act(dev(a), dev(ws), dev(sa), dev(sw), act, wbits, mpq.PER_ROW, want_absmax=False)
     assert none is None
-    np.testing.assert_array_equal(host(y), y_h if False else host(mpq.qgemm_act(dev(a), dev(ws), dev(sa), dev(sw), act, wbits, mpq.PER_ROW)[0]))
+    np.testing.assert_array_equal(host(y), host(mpq.qgemm_act(dev(a), dev(ws), dev(sa), dev(sw), act, wbits, mpq.PER_ROW)[0]))
 
 
 # ------------------------------------------------------- qgemm + activation + Eq. 1 in the epilogue
