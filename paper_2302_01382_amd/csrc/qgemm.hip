@@ -93,7 +93,6 @@ struct Stage8 { v4i c[2]; };
 // packed W tile: 128 rows x 32 B = 256 packed chunks, one per thread (expands to two chunks)
 struct Stage4 { v4i c; };
 
-template <bool FAST>
 __device__ __forceinline__ Stage8 load8(const int8_t* __restrict__ base, int64_t nrows, int64_t K,
                                         int64_t row0, int64_t k0) {
   Stage8 s;
@@ -105,15 +104,11 @@ __device__ __forceinline__ Stage8 load8(const int8_t* __restrict__ base, int64_t
     if (r >= nrows) r = nrows - 1;  // rows past the edge re-read the last row; never stored
     const int64_t k = k0 + ch * 16;
     const int8_t* p = base + r * K + k;
-    if (FAST) {
-      s.c[j] = (k < K) ? *reinterpret_cast<const v4i*>(p) : v4i{0, 0, 0, 0};
-    } else {
-      unsigned w[4] = {0, 0, 0, 0};
+    unsigned w[4] = {0, 0, 0, 0};
 #pragma unroll
-      for (int b = 0; b < 16; ++b)
-        if (k + b < K) w[b >> 2] |= (unsigned)(uint8_t)p[b] << (8 * (b & 3));
-      s.c[j] = v4i{(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
-    }
+    for (int b = 0; b < 16; ++b)
+      if (k + b < K) w[b >> 2] |= (unsigned)(uint8_t)p[b] << (8 * (b & 3));
+    s.c[j] = v4i{(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
   }
   return s;
 }
@@ -126,7 +121,6 @@ __device__ __forceinline__ void store8(int8_t* lds, const Stage8& s) {
   }
 }
 
-template <bool FAST>
 __device__ __forceinline__ Stage4 load4(const uint8_t* __restrict__ base, int64_t nrows, int64_t K,
                                         int64_t row0, int64_t k0) {
   Stage4 s;
@@ -135,15 +129,11 @@ __device__ __forceinline__ Stage4 load4(const uint8_t* __restrict__ base, int64_
   if (r >= nrows) r = nrows - 1;
   const int64_t k = k0 + half * 32;           // first k of this packed chunk (32 values)
   const uint8_t* p = base + r * (K >> 1) + (k >> 1);
-  if (FAST) {
-    s.c = (k < K) ? *reinterpret_cast<const v4i*>(p) : v4i{0, 0, 0, 0};
-  } else {
-    unsigned w[4] = {0, 0, 0, 0};
+  unsigned w[4] = {0, 0, 0, 0};
 #pragma unroll
-    for (int b = 0; b < 16; ++b)
-      if (k + 2 * b < K) w[b >> 2] |= (unsigned)p[b] << (8 * (b & 3));  // K even: pairs are whole
-    s.c = v4i{(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
-  }
+  for (int b = 0; b < 16; ++b)
+    if (k + 2 * b < K) w[b >> 2] |= (unsigned)p[b] << (8 * (b & 3));  // K even: pairs are whole
+  s.c = v4i{(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
   return s;
 }
 
@@ -160,7 +150,7 @@ __device__ __forceinline__ void store4(int8_t* lds, const Stage4& s) {
 
 // ---- the kernel ---------------------------------------------------------------------------------
 // grid: x = N tiles (fast index, so neighbouring blocks share the A row panel), y = M tiles.
-template <bool W4, bool FAST = false>  // FAST: whole 16-byte loads (aligned operands whose K is a multiple of the chunk); unused since those shapes take the LDS-DMA path
+template <bool W4>
 __global__ __launch_bounds__(kGemmThreads) void qgemm_k(const int8_t* __restrict__ A,
                                                         const void* __restrict__ Wv, int64_t M,
                                                         int64_t N, int64_t K,
@@ -186,11 +176,11 @@ __global__ __launch_bounds__(kGemmThreads) void qgemm_k(const int8_t* __restrict
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
-  Stage8 ra = load8<FAST>(A, M, K, m0, 0);
+  Stage8 ra = load8(A, M, K, m0, 0);
   Stage8 rb8;
   Stage4 rb4;
-  if (W4) rb4 = load4<FAST>(W4p, N, K, n0, 0);
-  else rb8 = load8<FAST>(W8, N, K, n0, 0);
+  if (W4) rb4 = load4(W4p, N, K, n0, 0);
+  else rb8 = load8(W8, N, K, n0, 0);
 
   for (int64_t k0 = 0; k0 < K; k0 += BK) {
     __syncthreads();  // previous step's LDS reads are done
@@ -199,9 +189,9 @@ __global__ __launch_bounds__(kGemmThreads) void qgemm_k(const int8_t* __restrict
     else store8(lds_b, rb8);
     __syncthreads();
     if (k0 + BK < K) {  // prefetch the next tile into registers while this one is multiplied
-      ra = load8<FAST>(A, M, K, m0, k0 + BK);
-      if (W4) rb4 = load4<FAST>(W4p, N, K, n0, k0 + BK);
-      else rb8 = load8<FAST>(W8, N, K, n0, k0 + BK);
+      ra = load8(A, M, K, m0, k0 + BK);
+      if (W4) rb4 = load4(W4p, N, K, n0, k0 + BK);
+      else rb8 = load8(W8, N, K, n0, k0 + BK);
     }
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
