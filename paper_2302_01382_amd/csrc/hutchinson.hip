@@ -15,8 +15,8 @@
 // probes the kernel is bound by that read (4 bytes per element of X against 64 flops), with 64
 // the fp32 matrix rate is level with it.  V (P x K floats, at most a few MB) stays in L2.
 //
-// A workgroup of four waves owns 32 rows of X at a time; the waves split k between them (a
-// contiguous quarter each) and walk it in chunks of 32 (lane l: row l % 32, sixteen consecutive k in half l / 32 of the chunk, loaded as four
+// A workgroup of eight waves owns 32 rows of X at a time; the waves split k between them (a
+// contiguous eighth each) and walk it in chunks of 32 (lane l: row l % 32, sixteen consecutive k in half l / 32 of the chunk, loaded as four
 // 16-byte pieces that feed four K = 2 matrix steps each), add their 32 x 32 partial products
 // through LDS, and wave 0 squares and accumulates.  Lane l of a product tile holds column
 // p = l % 32 and sixteen of the rows m, so the column sums of squares need no cross-lane work
@@ -28,7 +28,7 @@ namespace mpq {
 
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-constexpr int kHW = 4;           // waves per workgroup; they split k
+constexpr int kHW = 8;           // waves per workgroup; they split k
 constexpr int kProbeGroup = 64;  // probes per pass over X: the width at which the fp32 matrix rate
                                  // (64 flops per byte of X at the HBM rate) and the read of X balance
 
@@ -123,7 +123,7 @@ __global__ __launch_bounds__(kHW * 64, 4) void hutch_k(const float* __restrict__
   const int row = lane & 31, half = lane >> 5;
   const int64_t nchunk = (K + CK - 1) / CK;
   const int64_t nblk = (M + 31) >> 5;
-  // wave w takes the chunks [c_lo, c_hi): a contiguous quarter of k
+  // wave w takes the chunks [c_lo, c_hi): a contiguous share of k
   const int64_t per = (nchunk + kHW - 1) / kHW;
   const int64_t c_lo = wave * per;
   const int64_t c_hi = c_lo + per < nchunk ? c_lo + per : nchunk;
