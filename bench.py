@@ -528,10 +528,20 @@ def cpu_baseline(workloads, sample_rows):
         res = list(ex.map(one, range(n_layers)))
     wall = time.perf_counter() - t0
     total = sum(r[0] for r in res)
+    cpu = "unknown"
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                cpu = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    busy = sum(r[1] for r in res)
     return {
         "value": total / wall / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
         "sample": "cfg2 path on the first %d activation rows of each of the 8 layers, full weights; "
-                  "%.1f s wall, %.1f s summed over threads" % (sample_rows, wall, sum(r[1] for r in res)),
+                  "%.1f s wall, %.1f s summed over threads" % (sample_rows, wall, busy),
+        "value_per_thread": total / busy / 1e9, "cpu": cpu,
     }
 
 
