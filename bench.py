@@ -24,6 +24,8 @@ Other workloads (the parity-test configurations, measured with the same machiner
            cfg5-unfused: mpq_qgemm, torch GELU, mpq_calibrate_absmax, mpq_sse_pair)
     search  Alg. 1 / Alg. 2 over a 24-layer stack, evaluations per second
     latency qgemm latency table at batch 1 and the mixed-precision latency estimate built from it
+    gemm    mpq_qgemm on every configured GEMM shape: TOP/s, fraction of the matrix peak and of the
+            shape's own roofline
     hutchinson  Hessian-trace probe (random sign vectors, quadratic forms on the fp32 matrix cores)
 All inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 """
@@ -686,6 +688,42 @@ def run_hutchinson(torch, mpq, workloads, args):
     print(json.dumps(out))
 
 
+def run_gemm_shapes(torch, mpq, workloads, args):
+    """mpq_qgemm on every configured GEMM shape (configurations 2, 3 and 5, int8 and packed int4
+    weights, per-output-channel scales, fp32 output), operands rotated through more than the
+    memory-side cache holds: time per launch, TOP/s, fraction of the int8 matrix peak, and
+    fraction of the shape's own roofline min(matrix peak, arithmetic intensity x HBM peak)."""
+    from paper_2302_01382_amd import latency as lat
+    rows = []
+    for cfg, shapes in (("cfg2", workloads.CFG2), ("cfg3", workloads.CFG3), ("cfg5", workloads.CFG5)):
+        for g in shapes:
+            for st in (8, 4):
+                us = lat.time_qgemm(g.M, g.K, g.N, st, reps=30, warmup=4)
+                ops = 2.0 * g.M * g.N * g.K
+                nbytes = g.M * g.K + g.N * g.K * st // 8 + 4.0 * g.M * g.N
+                tops = ops / us / 1e6
+                roof_tops = min(INT8_PEAK_TOPS, ops / nbytes * HBM_PEAK_GBS / 1e3)
+                rows.append({"shape": "%s.%s" % (cfg, g.name), "M": g.M, "K": g.K, "N": g.N, "w_storage_bits": st,
+                             "us": round(us, 2), "tops": round(tops, 1), "frac_of_int8_mfma_peak": round(tops / INT8_PEAK_TOPS, 4),
+                             "roofline_tops": round(roof_tops, 1), "frac_of_own_roofline": round(tops / roof_tops, 4),
+                             "bound": "mfma" if roof_tops >= INT8_PEAK_TOPS else "hbm"})
+    best = max(rows, key=lambda r: r["tops"])
+    total_ops = sum(2.0 * r["M"] * r["N"] * r["K"] for r in rows)
+    total_us = sum(r["us"] for r in rows)
+    out = {
+        "metric": "qgemm int8 TOPS over the configured shapes (W8 and W4, cold operands)",
+        "value": total_ops / total_us / 1e6, "unit": "TOP/s", "n_gpus": 1, "steps": 30, "warmup": 4,
+        "ms_per_step": total_us / 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8 x int8 -> int32, fp32 epilogue", "data": "synthetic",
+        "config": {"workload": "gemm: the %d GEMM shapes of configurations 2, 3 and 5, int8 and packed int4 weights" % (len(rows) // 2)},
+        "roofline": {"bound": "mfma", "achieved": best["tops"], "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
+                     "frac": best["tops"] / INT8_PEAK_TOPS, "traffic": None,
+                     "kernel": "qgemm %s W%d" % (best["shape"], best["w_storage_bits"]), "avg_launch_us": best["us"]},
+        "shapes": rows,
+    }
+    print(json.dumps(out))
+
+
 def run_latency(torch, mpq, workloads, args):
     """Kernel latency table of mpq_qgemm at inference batch size one (the configured ResNet-50 and
     BERT-base layer shapes with M divided by their batch of 32) and the relative latency /
@@ -718,7 +756,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", choices=["cfg2", "cfg3", "cfg4", "cfg4-1stream", "cfg4-unfused", "cfg5", "cfg5-twopass", "cfg5-unfused", "search", "latency", "hutchinson"], default="cfg2")
+    ap.add_argument("--workload", choices=["cfg2", "cfg3", "cfg4", "cfg4-1stream", "cfg4-unfused", "cfg5", "cfg5-twopass", "cfg5-unfused", "search", "latency", "hutchinson", "gemm"], default="cfg2")
     ap.add_argument("--cpu-sample-rows", type=int, default=2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--streams", type=int, default=4,
@@ -749,6 +787,9 @@ def main():
         return
     if args.workload == "hutchinson":
         run_hutchinson(torch, mpq, workloads, args)
+        return
+    if args.workload == "gemm":
+        run_gemm_shapes(torch, mpq, workloads, args)
         return
     extra = {}
     traffic = None
