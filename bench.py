@@ -688,6 +688,30 @@ def run_hutchinson(torch, mpq, workloads, args):
     print(json.dumps(out))
 
 
+def measured_peaks(torch, mpq):
+    """What this chip sustains, measured in place: a plain device copy (HBM) and the int8 matrix
+    cores issuing from registers, on constant-byte and on uniformly random operands (the clock under
+    matrix load depends on how much the operand bits toggle)."""
+    n = mpq.diag_mfma_operand_bytes()
+    g = torch.Generator(device="cuda").manual_seed(3)
+    rnd = torch.randint(-127, 128, (n,), dtype=torch.int8, device="cuda", generator=g)
+    const = torch.full((n,), 3, dtype=torch.int8, device="cuda")
+    out = {"int8_mfma_tops_constant_bytes": round(mpq.diag_mfma_rate(const), 1),
+           "int8_mfma_tops_random_bytes": round(mpq.diag_mfma_rate(rnd), 1)}
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB, more than the memory-side cache
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    out["copy_gbs_read_plus_write"] = round(2 * src.numel() * 4 * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+    return out
+
+
 def run_gemm_shapes(torch, mpq, workloads, args):
     """mpq_qgemm on every configured GEMM shape (configurations 2, 3 and 5, int8 and packed int4
     weights, per-output-channel scales, fp32 output), operands rotated through more than the
@@ -708,6 +732,9 @@ def run_gemm_shapes(torch, mpq, workloads, args):
                              "roofline_tops": round(roof_tops, 1), "frac_of_own_roofline": round(tops / roof_tops, 4),
                              "bound": "mfma" if roof_tops >= INT8_PEAK_TOPS else "hbm"})
     best = max(rows, key=lambda r: r["tops"])
+    peaks = measured_peaks(torch, mpq)
+    for r in rows:
+        r["frac_of_measured_mfma_rate_random_bytes"] = round(r["tops"] / peaks["int8_mfma_tops_random_bytes"], 4)
     total_ops = sum(2.0 * r["M"] * r["N"] * r["K"] for r in rows)
     total_us = sum(r["us"] for r in rows)
     out = {
@@ -719,6 +746,7 @@ def run_gemm_shapes(torch, mpq, workloads, args):
         "roofline": {"bound": "mfma", "achieved": best["tops"], "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
                      "frac": best["tops"] / INT8_PEAK_TOPS, "traffic": None,
                      "kernel": "qgemm %s W%d" % (best["shape"], best["w_storage_bits"]), "avg_launch_us": best["us"]},
+        "measured_peaks": peaks,
         "shapes": rows,
     }
     print(json.dumps(out))
@@ -835,6 +863,7 @@ def main():
     }
     if "candidates_per_step" in extra:
         out["candidates_per_s"] = extra["candidates_per_step"] / (ms * 1e-3)
+    out["measured_peaks"] = measured_peaks(torch, mpq)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(workloads, args.cpu_sample_rows)
     print(json.dumps(out))

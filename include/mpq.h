@@ -300,6 +300,17 @@ int mpq_search_greedy(const int* order, int n_layers, const int* bit_widths, int
                       double target, int flags, mpq_eval_fn eval, void* user, int* config_out,
                       int* n_evals_out);
 
+/* ---- measurement aid (not part of the method) --------------------------------------------------
+ * Launches a kernel that does nothing but issue int8 matrix-core instructions (one workgroup of
+ * eight waves per CU, 16 x iters instructions per wave) on operand registers filled once from
+ * `operands` (device, 16-byte aligned, at least mpq_diag_mfma_operand_bytes() bytes).  Timing it
+ * gives the matrix rate this chip sustains for operands of that kind: the clock under matrix load
+ * depends on how much the operand bits toggle.  ops_out (host, nullable) receives the number of
+ * integer operations the launch performs (2 per multiply-add).  sink: device int[1], scratch. */
+size_t mpq_diag_mfma_operand_bytes(void);
+int mpq_diag_mfma_rate(const void* operands, size_t operand_bytes, int iters, int* sink, double* ops_out,
+                       void* stream);
+
 #ifdef __cplusplus
 }
 #endif

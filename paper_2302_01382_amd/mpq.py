@@ -24,7 +24,7 @@ EXPORTS = [
     "mpq_sse_pair_workspace_bytes", "mpq_sse_pair", "mpq_qgemm_score_workspace_bytes", "mpq_qgemm_score",
     "mpq_search_bisection", "mpq_search_greedy", "mpq_noise_inject_sweep",
     "mpq_fake_quant_scales", "mpq_scale_grad_workspace_bytes", "mpq_scale_grad", "mpq_scale_sgd_step", "mpq_qgemm_act", "mpq_qgemm_act_codes",
-    "mpq_fake_quant_step", "mpq_stack_evaluate_workspace_bytes", "mpq_stack_evaluate", "mpq_rademacher", "mpq_hutchinson_quad_workspace_bytes", "mpq_hutchinson_quad", "mpq_hutchinson_quad_signs",
+    "mpq_diag_mfma_operand_bytes", "mpq_diag_mfma_rate", "mpq_fake_quant_step", "mpq_stack_evaluate_workspace_bytes", "mpq_stack_evaluate", "mpq_rademacher", "mpq_hutchinson_quad_workspace_bytes", "mpq_hutchinson_quad", "mpq_hutchinson_quad_signs",
 ]
 
 ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
@@ -79,6 +79,9 @@ def lib():
         L.mpq_scale_sgd_step.argtypes = [vp, vp, vp, vp, i64, C.c_double, vp]
         L.mpq_qgemm_act.argtypes = [vp, vp, ci, i64, i64, i64, vp, vp, ci, ci, vp, vp, ci, vp]
         L.mpq_qgemm_act_codes.argtypes = [vp, vp, ci, i64, i64, i64, vp, vp, ci, ci, vp, ci, vp, vp]
+        L.mpq_diag_mfma_operand_bytes.argtypes = []
+        L.mpq_diag_mfma_operand_bytes.restype = C.c_size_t
+        L.mpq_diag_mfma_rate.argtypes = [vp, C.c_size_t, ci, vp, C.POINTER(C.c_double), vp]
         L.mpq_fake_quant_step.argtypes = [vp, i64, i64, vp, ci, vp, vp, vp, vp, vp]
         L.mpq_stack_evaluate_workspace_bytes.argtypes = [vp, ci, i64]
         L.mpq_stack_evaluate_workspace_bytes.restype = C.c_size_t
@@ -368,6 +371,33 @@ def stack_evaluate_workspace_bytes(plan: "StackPlan") -> int:
 def stack_evaluate(plan: "StackPlan", width_index, sse_out, ws: "Workspace" = None):
     """One evaluation of a stack (see StackPlan): layer l at its candidate width number width_index[l]."""
     return plan.evaluate(width_index, sse_out, ws)
+
+
+def diag_mfma_operand_bytes() -> int:
+    return int(lib().mpq_diag_mfma_operand_bytes())
+
+
+def diag_mfma_rate(operands, iters: int = 2048, reps: int = 5) -> float:
+    """Measured int8 matrix-core issue rate in TOP/s for operand registers filled from `operands`
+    (device int8 tensor of at least diag_mfma_operand_bytes() bytes): a measurement aid."""
+    torch = _torch()
+    sink = torch.zeros(1, dtype=torch.int32, device=operands.device)
+    ops = C.c_double(0.0)
+    nbytes = operands.numel() * operands.element_size()
+
+    def launch():
+        _check(lib().mpq_diag_mfma_rate(_ptr(operands), nbytes, iters, _ptr(sink), C.byref(ops), _stream()),
+               "mpq_diag_mfma_rate")
+
+    launch()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        launch()
+    e1.record()
+    torch.cuda.synchronize()
+    return ops.value * reps / (e0.elapsed_time(e1) * 1e-3) / 1e12
 
 
 def hutchinson_quad_workspace_bytes(M, K, P) -> int:

@@ -107,6 +107,19 @@ def test_fake_quant_validation():
 
 
 @needs_no_gpu
+def test_diag_mfma_rate_validation():
+    L = mpq.lib()
+    need = L.mpq_diag_mfma_operand_bytes()
+    assert need == 256 * 8 * 64 * 8 * 16
+    f = L.mpq_diag_mfma_rate
+    assert f(None, need, 16, FAKE, None, None) == mpq.ERR_NULL
+    assert f(FAKE16, need, 16, None, None, None) == mpq.ERR_NULL
+    assert f(FAKE16, need - 1, 16, FAKE, None, None) == mpq.ERR_WORKSPACE
+    assert f(C.c_void_p(0x10008), need, 16, FAKE, None, None) == mpq.ERR_ALIGN
+    assert f(FAKE16, need, 0, FAKE, None, None) == mpq.ERR_SHAPE
+
+
+@needs_no_gpu
 def test_fake_quant_step_validation():
     f = mpq.lib().mpq_fake_quant_step
     assert f(FAKE, 4, 4, FAKE, 8, FAKE, None, None, None, None) == mpq.ERR_NULL           # no step_out
