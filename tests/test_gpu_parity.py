@@ -308,6 +308,16 @@ def test_qgemm_large_tiles_on_sampled_rows(mnk, wbits):
     # cheap global invariant instead: column sums of acc equal (sum of A rows) . W
     colsum = a.astype(np.int64).sum(0) @ w.astype(np.int64).T
     np.testing.assert_array_equal(host(acc).astype(np.int64).sum(0), colsum)
+    # per-channel scales or an output that are only 4-byte aligned take the scalar epilogue: same bits
+    y_s, _ = mpq.qgemm(dev(a), dev(ws), dev(sa), dev_misaligned(sw), wbits, mpq.PER_ROW)
+    np.testing.assert_array_equal(host(y_s), host(y))
+    y_buf = dev_misaligned(np.zeros((M, N), np.float32))
+    mpq.qgemm(dev(a), dev(ws), dev(sa), dev(sw), wbits, mpq.PER_ROW, y=y_buf)
+    np.testing.assert_array_equal(host(y_buf), host(y))
+    # one scale for the whole weight tensor
+    y_t, _ = mpq.qgemm(dev(a), dev(ws), dev(sa), dev(sw[:1].copy()), wbits, mpq.PER_TENSOR)
+    y_to, _ = oracle.qgemm(a[rows], ws, sa, sw[:1], wbits, oracle.PER_TENSOR)
+    np.testing.assert_allclose(host(y_t)[rows], y_to, rtol=RTOL_Y, atol=0)
 
 
 def test_qgemm_extreme_operands_and_single_outputs():
