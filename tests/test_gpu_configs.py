@@ -27,6 +27,10 @@ def host(t):
     return t.cpu().numpy()
 
 
+def t_equal(a, b):
+    return bool(torch().equal(a, b))
+
+
 def sample_rows(M, n, seed):
     r = np.random.Generator(np.random.PCG64(seed))
     edge = [0, 1, 63, 64, 127, 128, 255, 256, M - 257, M - 256, M - 129, M - 2, M - 1]
@@ -70,8 +74,16 @@ def check_layer(a, w, bits_a, bits_w, w_gran, seed, n_rows=96):
     np.testing.assert_array_equal(host(acc)[rows], acc_o)
     np.testing.assert_allclose(y_h[rows], y_o, rtol=RTOL_Y, atol=0)
     y_ref = da @ dw.t()
+    want = oracle.sse_pair(y_h, host(y_ref))
     got = host(mpq.sse_pair(y, y_ref))[0]
-    assert got == pytest.approx(oracle.sse_pair(y_h, host(y_ref)), rel=RTOL_SSE)
+    assert got == pytest.approx(want, rel=RTOL_SSE)
+    # the fused forms on the same full-size layer: the quantizer kernel that also leaves the step
+    # size (what the benchmark times), and one GEMM that writes Y and takes the score in its epilogue
+    _, ca2, _, sa2 = mpq.fake_quant_step(da, am_a, bits_a, want_y=False, want_codes=True)
+    assert t_equal(ca2, ca) and t_equal(sa2, sa)
+    fused, y2 = mpq.qgemm_score(ca2, cw if store == 8 else pw, sa2, sw, y_ref, store, w_gran, want_y=True)
+    assert t_equal(y2, y)
+    assert host(fused)[0] == pytest.approx(want, rel=RTOL_SSE)
 
 
 @pytest.mark.parametrize("idx", range(len(workloads.CFG2)))
