@@ -25,13 +25,24 @@ OK, BAD_ARG, ACC_OVERFLOW = 0, 1, 2
 CXXFLAGS = ["-std=c++17", "-O2", "-ffp-contract=off", "-fPIC", "-shared", "-Wall", "-Wextra"]
 
 
+# MPQ_ORACLE_SANITIZE=1 builds (and loads) a second copy of the oracle instrumented with the address and
+# undefined-behaviour sanitizers.  Python itself is not instrumented, so the sanitizer runtime has
+# to be in the process first:
+#   LD_PRELOAD=$(gcc -print-file-name=libasan.so) ASAN_OPTIONS=detect_leaks=0 MPQ_ORACLE_SANITIZE=1 \
+#       python -m pytest tests -m "not gpu"
+SANITIZE = os.environ.get("MPQ_ORACLE_SANITIZE", "0") not in ("", "0")
+_SAN_LIB = os.path.join(_HERE, "libmpq_oracle_san.so")
+SAN_FLAGS = ["-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer", "-g"]
+
+
 def build(force: bool = False) -> str:
-    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    out = _SAN_LIB if SANITIZE else _LIB
+    stale = (not os.path.exists(out)) or os.path.getmtime(out) < os.path.getmtime(_SRC)
     if force or stale:
-        tmp = _LIB + ".tmp%d" % os.getpid()
-        subprocess.check_call(["g++", *CXXFLAGS, "-o", tmp, _SRC])
-        os.replace(tmp, _LIB)
-    return _LIB
+        tmp = out + ".tmp%d" % os.getpid()
+        subprocess.check_call(["g++", *CXXFLAGS, *(SAN_FLAGS if SANITIZE else []), "-o", tmp, _SRC])
+        os.replace(tmp, out)
+    return out
 
 
 _lib = None

@@ -174,6 +174,32 @@ def test_quant_error_sub_ranges_foreign_absmax_and_reproducibility():
         np.testing.assert_array_equal(a, b)  # fixed combination order: same bits every run
 
 
+
+def test_quant_error_of_a_tensor_on_the_grid_is_exactly_zero():
+    """Eq. 2 over the reals: a tensor made of grid points code * scale_b has SSE_b == 0.  With a
+    power-of-two step the tensor is exact in fp32 and both sides must return 0.0, not 1e-15."""
+    r = np.random.Generator(np.random.PCG64(31))
+    for b in range(2, 9):
+        q = (1 << (b - 1)) - 1
+        codes = r.integers(-q, q + 1, size=(301, 1028))
+        codes[0, 0] = q
+        x = (codes * np.float32(2.0 ** -5)).astype(np.float32)
+        for gran in GRANS:
+            am = oracle.absmax(x, gran)
+            keep = am == np.float32(q * 2.0 ** -5)              # channels whose maximum code is qmax
+            want = oracle.quant_error(x, am, 2, 8, gran)
+            got = host(mpq.quant_error(dev(x), dev(am), 2, 8, gran))
+            assert np.all(want[keep, b - 2] == 0.0) and np.all(got[keep, b - 2] == 0.0)
+            np.testing.assert_allclose(got, want, rtol=RTOL_SSE, atol=1e-30)
+    # full-mantissa step: the sum of squared product roundings, tiny but not zero, on both sides
+    am = np.array([0.7321], np.float32)
+    s8 = oracle.scale_from_absmax(am, 8)[0]
+    x = (r.integers(-127, 128, size=(300, 1028)).astype(np.float32) * s8).astype(np.float32)
+    want = oracle.quant_error(x, am, 8, 8)
+    assert 0.0 < want[0, 0] < 1e-9
+    np.testing.assert_allclose(host(mpq.quant_error(dev(x), dev(am), 8, 8)), want, rtol=RTOL_SSE, atol=0)
+
+
 def test_quant_error_argmin_bit_selection_matches_oracle():
     """Smallest b whose E_QE (Eq. 2) is below a threshold, and the ordering of tensors by E_QE."""
     tensors = [data((64, 256), 20 + i, s) for i, s in enumerate((1.0, 0.05, 3.0, 0.5))]

@@ -215,6 +215,41 @@ def test_sse_brute_force_closed_form_and_invariances():
     assert 3.0 < sse[0, 4] / sse[0, 5] < 5.0 and 6.0 < sse[0, 0] / sse[0, 1] < 12.0
 
 
+
+def test_sse_of_a_tensor_lying_on_the_grid():
+    """Eq. 2 is stated over the reals: Q_b(x) inside the sum is the grid point code * scale_b itself.
+    A tensor whose every element is such a grid point therefore has SSE_b == 0 exactly.  With a
+    power-of-two step (m = qmax_b * 2^-k) every grid point is an fp32 number, so the case can be
+    built without rounding; the other bit-widths of the same sweep see an off-grid tensor."""
+    r = rng(31)
+    for b in range(2, 9):
+        q = QMAX[b]
+        step = np.float32(2.0 ** -5)
+        codes = r.integers(-q, q + 1, size=(37, 53))
+        codes[0, 0], codes[0, 1] = q, -q                      # the absmax is attained
+        x = (codes * step).astype(np.float32)                 # exact products
+        m = oracle.absmax(x)
+        assert float(m[0]) == q * float(step)
+        s_b, inv_b = oracle.bit_constants(float(m[0]), b)
+        assert float(s_b) == float(step) and float(inv_b) == 1.0 / float(step)
+        _, c, _ = oracle.fake_quant(x, m, b)
+        np.testing.assert_array_equal(c, codes)
+        sse = oracle.quant_error(x, m)[0]
+        assert sse[b - 2] == 0.0
+        if b < 8 and b > 2:
+            assert sse[b - 3] > 0.0                            # a coarser grid does not contain it
+    # a step with a full mantissa: x = fl32(code * step) is the grid point rounded once, so the
+    # sum is the sum of the squared rounding errors of those products -- tiny, not zero
+    m = np.array([0.7321], np.float32)
+    s8, _ = oracle.bit_constants(float(m[0]), 8)
+    codes = r.integers(-127, 128, size=(64, 64))
+    x = (codes.astype(np.float32) * s8).astype(np.float32)
+    want = math.fsum(((codes.astype(np.float64) * np.float64(s8) - x.astype(np.float64)) ** 2).ravel().tolist())
+    got = oracle.quant_error(x, m, 8, 8)[0, 0]
+    assert 0.0 < want < (2.0 ** -24 * 0.7321) ** 2 * x.size
+    assert got == pytest.approx(want, rel=1e-12)
+
+
 def test_per_channel_sse_adds_up_and_uses_the_right_axis():
     r = rng(9)
     x = r.standard_normal((12, 20)).astype(np.float32)
