@@ -46,7 +46,8 @@ enum mpq_status {
   MPQ_ERR_ALIGN = 4,     /* a pointer lacks the alignment stated for it */
   MPQ_ERR_WORKSPACE = 5, /* ws is NULL or ws_bytes too small */
   MPQ_ERR_GRAN = 6,      /* granularity value not valid for this call */
-  MPQ_ERR_HIP = 7        /* the HIP runtime refused a launch; see mpq_last_hip_error() */
+  MPQ_ERR_HIP = 7,       /* the HIP runtime refused a launch; see mpq_last_hip_error() */
+  MPQ_ERR_TOO_LARGE = 8  /* the input needs more scratch than a built-in buffer of fixed size holds */
 };
 
 enum mpq_gran { MPQ_PER_TENSOR = 0, MPQ_PER_ROW = 1, MPQ_PER_COL = 2 };
@@ -104,6 +105,24 @@ int mpq_fake_quant_step(const float* x, int64_t rows, int64_t cols, const float*
 size_t mpq_quant_error_workspace_bytes(int64_t rows, int64_t cols, int gran, int b_lo, int b_hi);
 int mpq_quant_error(const float* x, int64_t rows, int64_t cols, int gran, const float* absmax,
                     int b_lo, int b_hi, double* sse_out, void* ws, size_t ws_bytes, void* stream);
+
+/* mpq_quant_error for callers that cannot allocate device memory and have no workspace to hand
+ * over: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments (minus the workspace), same kernels and bit-for-bit the same results as
+ * mpq_quant_error; the partial sums go to a buffer of MPQ_NOALLOC_SCRATCH_BYTES that is part of the
+ * library's device image (each GPU the library runs on holds one copy until the process ends).
+ * The call allocates nothing and calls no allocating routine; on the first call on a device it
+ * looks up that device's address of the buffer (one symbol query, cached), with the caller's
+ * current device.  Inputs whose partial sums do not fit -- mpq_quant_error_workspace_bytes(...) >
+ * MPQ_NOALLOC_SCRATCH_BYTES (4 MiB), which only happens for MPQ_PER_COL (from about 1500 columns
+ * on) or rows longer than 16384 columns on large tensors; the per-tensor sweep of any size needs at
+ * most 56 KiB and the per-row sweep of rows up to 16384 columns none -- are rejected with
+ * MPQ_ERR_TOO_LARGE before anything is launched.  All calls on one GPU share the one buffer:
+ * calls that may run concurrently on the same GPU (different streams, different host threads)
+ * race on it and must be serialised by the caller; calls in stream order are safe. */
+#define MPQ_NOALLOC_SCRATCH_BYTES ((size_t)4 << 20)
+int mpq_quant_error_noalloc(const float* x, int64_t rows, int64_t cols, int gran, const float* absmax,
+                            int b_lo, int b_hi, double* sse_out, void* stream);
 
 /* ---- Sec. 3.2.2 Eq. 3-5: Gaussian perturbation ----------------------------------------------
  * y[i] = fl32(x[i] + sigma_ch * z_i), sigma_ch = fl32(lambda * scale_bits(absmax[ch])): the

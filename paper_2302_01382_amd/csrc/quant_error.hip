@@ -14,6 +14,8 @@
 // atomics anywhere.
 #include "common.hpp"
 
+#include <mutex>
+
 namespace mpq {
 
 constexpr int64_t kSeg = 16384;  // columns per wave item in the per-row kernels
@@ -367,16 +369,16 @@ extern "C" size_t mpq_quant_error_workspace_bytes(int64_t rows, int64_t cols, in
   return (size_t)g.partial_doubles * sizeof(double);
 }
 
-extern "C" int mpq_quant_error(const float* x, int64_t rows, int64_t cols, int gran,
-                               const float* absmax, int b_lo, int b_hi, double* sse_out, void* ws,
-                               size_t ws_bytes, void* stream) {
+static int run_quant_error(const float* x, int64_t rows, int64_t cols, int gran, const float* absmax, int b_lo,
+                           int b_hi, double* sse_out, void* ws, size_t ws_bytes, bool builtin_scratch,
+                           void* stream) {
   if (!x || !absmax || !sse_out) return MPQ_ERR_NULL;
   const int rc = check_qe_args(rows, cols, gran, b_lo, b_hi);
   if (rc != MPQ_OK) return rc;
   const int nb = b_hi - b_lo + 1;
   const QeGeom g = qe_geometry(rows, cols, gran, nb, aligned16(x));
   const size_t need = (size_t)g.partial_doubles * sizeof(double);
-  if (need > 0 && (!ws || ws_bytes < need)) return MPQ_ERR_WORKSPACE;
+  if (need > 0 && (!ws || ws_bytes < need)) return builtin_scratch ? MPQ_ERR_TOO_LARGE : MPQ_ERR_WORKSPACE;
   if (need > 0 && !aligned16(ws)) return MPQ_ERR_ALIGN;
   if ((reinterpret_cast<uintptr_t>(sse_out) & 7u) != 0) return MPQ_ERR_ALIGN;
   hipStream_t st = (hipStream_t)stream;
@@ -391,6 +393,64 @@ extern "C" int mpq_quant_error(const float* x, int64_t rows, int64_t cols, int g
     default: launch_qe<7>(g, x, rows, cols, gran, absmax, b_lo, sse_out, wsd, st); break;
   }
   return launch_status();
+}
+
+extern "C" int mpq_quant_error(const float* x, int64_t rows, int64_t cols, int gran,
+                               const float* absmax, int b_lo, int b_hi, double* sse_out, void* ws,
+                               size_t ws_bytes, void* stream) {
+  return run_quant_error(x, rows, cols, gran, absmax, b_lo, b_hi, sse_out, ws, ws_bytes, false, stream);
+}
+
+// ---- the sweep for callers that cannot allocate -------------------------------------------------
+// The partial sums live in a buffer that is part of the library's device image, so the call needs
+// neither a workspace from the caller nor any allocation.  Every GPU the library runs on holds its
+// own copy of the buffer, at its own address, for the life of the process.  In host code the
+// array's name is only a handle for hipGetSymbolAddress: the device address is looked up once per
+// device (with that device current) and kept; everything that touches the memory uses that pointer.
+constexpr size_t kScratchBytes = MPQ_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// device address of `scratch` on the current device
+int scratch_of_current_device(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    set_last_hip_error((int)(e != hipSuccess ? e : hipErrorInvalidDevice));
+    return MPQ_ERR_HIP;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+      set_last_hip_error((int)(e != hipSuccess ? e : hipErrorInvalidSymbol));
+      return MPQ_ERR_HIP;
+    }
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return MPQ_OK;
+}
+}  // namespace
+
+extern "C" int mpq_quant_error_noalloc(const float* x, int64_t rows, int64_t cols, int gran, const float* absmax,
+                                       int b_lo, int b_hi, double* sse_out, void* stream) {
+  // arguments first: a call that cannot succeed must not touch the device at all
+  if (!x || !absmax || !sse_out) return MPQ_ERR_NULL;
+  int rc = check_qe_args(rows, cols, gran, b_lo, b_hi);
+  if (rc != MPQ_OK) return rc;
+  if (mpq_quant_error_workspace_bytes(rows, cols, gran, b_lo, b_hi) > kScratchBytes) return MPQ_ERR_TOO_LARGE;
+  void* ptr = nullptr;
+  rc = scratch_of_current_device(&ptr);
+  if (rc != MPQ_OK) return rc;
+  // every partial the finishing kernel reads is written by the main kernel of the same call:
+  // nothing in the buffer has to start at zero
+  return run_quant_error(x, rows, cols, gran, absmax, b_lo, b_hi, sse_out, ptr, kScratchBytes, true, stream);
 }
 
 extern "C" size_t mpq_sse_pair_workspace_bytes(int64_t n) {

@@ -18,6 +18,7 @@ const char* mpq_strerror(int status) {
     case MPQ_ERR_WORKSPACE: return "workspace missing or too small";
     case MPQ_ERR_GRAN: return "granularity not valid for this call";
     case MPQ_ERR_HIP: return "HIP runtime error on launch";
+    case MPQ_ERR_TOO_LARGE: return "input needs more scratch than the library's built-in buffer holds";
     default: return "unknown status";
   }
 }

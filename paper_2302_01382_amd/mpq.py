@@ -14,13 +14,14 @@ from . import build as _build
 
 PER_TENSOR, PER_ROW, PER_COL = 0, 1, 2
 OK = 0
-ERR_NULL, ERR_SHAPE, ERR_BITS, ERR_ALIGN, ERR_WORKSPACE, ERR_GRAN, ERR_HIP = 1, 2, 3, 4, 5, 6, 7
+ERR_NULL, ERR_SHAPE, ERR_BITS, ERR_ALIGN, ERR_WORKSPACE, ERR_GRAN, ERR_HIP, ERR_TOO_LARGE = 1, 2, 3, 4, 5, 6, 7, 8
+NOALLOC_SCRATCH_BYTES = 4 << 20
 
 EXPORTS = [
     "mpq_strerror", "mpq_last_hip_error", "mpq_version", "mpq_calibrate_absmax_workspace_bytes",
     "mpq_calibrate_absmax",
     "mpq_scale_from_absmax", "mpq_fake_quant", "mpq_quant_error_workspace_bytes",
-    "mpq_quant_error", "mpq_noise_inject", "mpq_qgemm_workspace_bytes", "mpq_qgemm",
+    "mpq_quant_error", "mpq_quant_error_noalloc", "mpq_noise_inject", "mpq_qgemm_workspace_bytes", "mpq_qgemm",
     "mpq_sse_pair_workspace_bytes", "mpq_sse_pair", "mpq_qgemm_score_workspace_bytes", "mpq_qgemm_score",
     "mpq_search_bisection", "mpq_search_greedy", "mpq_noise_inject_sweep",
     "mpq_fake_quant_scales", "mpq_scale_grad_workspace_bytes", "mpq_scale_grad", "mpq_scale_sgd_step", "mpq_qgemm_act", "mpq_qgemm_act_codes",
@@ -70,6 +71,7 @@ def lib():
         L.mpq_quant_error_workspace_bytes.restype = sz
         L.mpq_quant_error_workspace_bytes.argtypes = [i64, i64, ci, ci, ci]
         L.mpq_quant_error.argtypes = [vp, i64, i64, ci, vp, ci, ci, vp, vp, sz, vp]
+        L.mpq_quant_error_noalloc.argtypes = [vp, i64, i64, ci, vp, ci, ci, vp, vp]
         L.mpq_noise_inject.argtypes = [vp, i64, i64, ci, vp, ci, C.c_float, C.c_uint64, C.c_uint64, vp, vp]
         L.mpq_noise_inject_sweep.argtypes = [vp, i64, i64, ci, vp, ci, ci, C.c_float, C.c_uint64, C.c_uint64, vp, i64, vp]
         L.mpq_fake_quant_scales.argtypes = [vp, i64, i64, ci, vp, vp, ci, vp, vp, vp]
@@ -239,6 +241,15 @@ def quant_error(x, absmax, b_lo=2, b_hi=8, gran=PER_TENSOR, out=None, ws: Worksp
     wp, wn = (ws or _default_ws).get(quant_error_workspace_bytes(rows, cols, gran, b_lo, b_hi))
     _check(lib().mpq_quant_error(_ptr(x), rows, cols, gran, _ptr(absmax), b_lo, b_hi, _ptr(out), wp,
                                  wn, _stream()), "mpq_quant_error")
+    return out
+
+
+def quant_error_noalloc(x, absmax, out, b_lo=2, b_hi=8, gran=PER_TENSOR):
+    """quant_error without a workspace and without any allocation, here or in the library: the
+    caller passes the float64 [nch, nb] output; partial sums go to the library's built-in buffer."""
+    rows, cols = x.shape
+    _check(lib().mpq_quant_error_noalloc(_ptr(x), rows, cols, gran, _ptr(absmax), b_lo, b_hi, _ptr(out),
+                                         _stream()), "mpq_quant_error_noalloc")
     return out
 
 

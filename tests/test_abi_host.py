@@ -65,7 +65,7 @@ def test_strerror_and_version():
     L = mpq.lib()
     assert L.mpq_version() >= 100
     seen = set()
-    for code in range(0, 8):
+    for code in range(0, 9):
         s = L.mpq_strerror(code).decode()
         assert s and s not in seen
         seen.add(s)
