@@ -124,6 +124,53 @@ int mpq_quant_error(const float* x, int64_t rows, int64_t cols, int gran, const 
 int mpq_quant_error_noalloc(const float* x, int64_t rows, int64_t cols, int gran, const float* absmax,
                             int b_lo, int b_hi, double* sse_out, void* stream);
 
+/* ---- Sec. 3.2.1, "for each tensor": calibration and Eq. 2 over a whole SET of tensors -------------
+ * The sensitivity ordering needs max|x| and the error sums of every weight tensor of the model.
+ * These calls cover all tensors of a set in two or three launches instead of several per tensor
+ * (a model's tensors are a few MB each: alone, each kernel is mostly launch ramp and tail).
+ *
+ * The set is described once by a PLAN.  mpq_sweep_plan_build() writes it into HOST memory of the
+ * caller (size from mpq_sweep_plan_bytes(), 8-byte aligned); the caller copies those bytes,
+ * unchanged, to DEVICE memory (8-byte aligned) and passes both copies to the calls below: the host
+ * copy is what the library validates and sizes its grids from, the device copy is what the kernels
+ * read.  The plan holds the descriptors and a table of work items; it stays valid as long as the
+ * tensors' addresses and shapes do, for any number of calls.  The library allocates and copies
+ * nothing.
+ *
+ * mpq_sweep_tensor (HOST struct of DEVICE pointers):
+ *   x [rows x cols] fp32, 16-byte aligned, cols a multiple of 4 and at most 16384 (other tensors go
+ *   through the single-tensor calls); absmax_row float[rows] and absmax_tensor float[1]: written by
+ *   mpq_calibrate_absmax_batch, read by mpq_quant_error_batch (both required, 4-byte aligned);
+ *   sse_tensor double[nb], sse_row double[rows x nb] (row-major, b ascending): written by
+ *   mpq_quant_error_batch, each required only for the granularity that writes it (8-byte aligned).
+ *
+ * mpq_calibrate_absmax_batch: absmax_row[r] = max_c |x[r][c]|, absmax_tensor[0] = max_r absmax_row[r]
+ *   (= max |x|; exact), for every tensor of the plan; one read of the tensors.  No workspace.
+ * mpq_quant_error_batch: Eq. 2's sums for b = b_lo..b_hi in one read per tensor, with
+ *   gran = MPQ_PER_TENSOR: sse_tensor, quantizer scale from absmax_tensor;
+ *   gran = MPQ_PER_ROW:    sse_row, scale from absmax_row (bit-identical to mpq_quant_error per tensor);
+ *   gran = MPQ_SWEEP_TENSOR_AND_ROW: both from the same read (twice the arithmetic per element).
+ *   fp32 per-lane partial sums, fixed-order double combine: reproducible from call to call.
+ *   Workspace from the query (0 for MPQ_PER_ROW), 8-byte aligned.
+ * Errors: MPQ_ERR_NULL / _SHAPE / _ALIGN for a tensor the plan cannot hold (build), MPQ_ERR_SHAPE
+ * for a plan_host that is not a built plan, MPQ_ERR_WORKSPACE, MPQ_ERR_GRAN, MPQ_ERR_BITS. */
+typedef struct mpq_sweep_tensor {
+  const float* x;
+  int64_t rows, cols;
+  float* absmax_row;
+  float* absmax_tensor;
+  double* sse_tensor;
+  double* sse_row;
+} mpq_sweep_tensor;
+enum mpq_sweep_gran { MPQ_SWEEP_TENSOR_AND_ROW = 3 };
+size_t mpq_sweep_plan_bytes(const mpq_sweep_tensor* tensors /* host */, int n_tensors);
+int mpq_sweep_plan_build(const mpq_sweep_tensor* tensors /* host */, int n_tensors, void* plan_host,
+                         size_t plan_host_bytes);
+int mpq_calibrate_absmax_batch(const void* plan_host, const void* plan_dev, void* stream);
+size_t mpq_quant_error_batch_workspace_bytes(const void* plan_host, int gran, int b_lo, int b_hi);
+int mpq_quant_error_batch(const void* plan_host, const void* plan_dev, int gran, int b_lo, int b_hi,
+                          void* ws, size_t ws_bytes, void* stream);
+
 /* ---- Sec. 3.2.2 Eq. 3-5: Gaussian perturbation ----------------------------------------------
  * y[i] = fl32(x[i] + sigma_ch * z_i), sigma_ch = fl32(lambda * scale_bits(absmax[ch])): the
  * noise standard deviation is `lambda` quantization steps of the b-bit grid.  z_i is the i-th

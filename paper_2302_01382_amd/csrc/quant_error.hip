@@ -13,37 +13,13 @@
 // DPP wave reduction, then double precision across waves / blocks in a fixed order.  No float
 // atomics anywhere.
 #include "common.hpp"
+#include "sweep.hpp"
 
 #include <mutex>
 
 namespace mpq {
 
 constexpr int64_t kSeg = 16384;  // columns per wave item in the per-row kernels
-
-template <int NB>
-struct Sweep {
-  float m;
-  float inv[NB], sc[NB], acc[NB];
-  __device__ __forceinline__ void init(float absmax, int b_lo) {
-    m = absmax;
-#pragma unroll
-    for (int b = 0; b < NB; ++b) {
-      bit_constants(absmax, b_lo + b, sc[b], inv[b]);
-      acc[b] = 0.0f;
-    }
-  }
-  __device__ __forceinline__ void add(float v) {
-    const float vc = __builtin_amdgcn_fmed3f(v, -m, m);
-#pragma unroll
-    for (int b = 0; b < NB; ++b) {
-      const float t = __builtin_fmaf(vc, inv[b], kMagic);
-      const float q = t - kMagic;
-      const float e = __builtin_fmaf(q, sc[b], -v);
-      acc[b] = __builtin_fmaf(e, e, acc[b]);
-    }
-  }
-  __device__ __forceinline__ void add4(const float4 v) { add(v.x); add(v.y); add(v.z); add(v.w); }
-};
 
 // ---- per tensor ----------------------------------------------------------------------------
 // partials: double [gridDim.x][NB]

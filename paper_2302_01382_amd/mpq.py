@@ -21,7 +21,9 @@ EXPORTS = [
     "mpq_strerror", "mpq_last_hip_error", "mpq_version", "mpq_calibrate_absmax_workspace_bytes",
     "mpq_calibrate_absmax",
     "mpq_scale_from_absmax", "mpq_fake_quant", "mpq_quant_error_workspace_bytes",
-    "mpq_quant_error", "mpq_quant_error_noalloc", "mpq_noise_inject", "mpq_qgemm_workspace_bytes", "mpq_qgemm",
+    "mpq_quant_error", "mpq_quant_error_noalloc", "mpq_noise_inject",
+    "mpq_sweep_plan_bytes", "mpq_sweep_plan_build", "mpq_calibrate_absmax_batch",
+    "mpq_quant_error_batch_workspace_bytes", "mpq_quant_error_batch", "mpq_qgemm_workspace_bytes", "mpq_qgemm",
     "mpq_sse_pair_workspace_bytes", "mpq_sse_pair", "mpq_qgemm_score_workspace_bytes", "mpq_qgemm_score",
     "mpq_search_bisection", "mpq_search_greedy", "mpq_noise_inject_sweep",
     "mpq_fake_quant_scales", "mpq_scale_grad_workspace_bytes", "mpq_scale_grad", "mpq_scale_sgd_step", "mpq_qgemm_act", "mpq_qgemm_act_codes",
@@ -72,6 +74,13 @@ def lib():
         L.mpq_quant_error_workspace_bytes.argtypes = [i64, i64, ci, ci, ci]
         L.mpq_quant_error.argtypes = [vp, i64, i64, ci, vp, ci, ci, vp, vp, sz, vp]
         L.mpq_quant_error_noalloc.argtypes = [vp, i64, i64, ci, vp, ci, ci, vp, vp]
+        L.mpq_sweep_plan_bytes.restype = sz
+        L.mpq_sweep_plan_bytes.argtypes = [vp, ci]
+        L.mpq_sweep_plan_build.argtypes = [vp, ci, vp, sz]
+        L.mpq_calibrate_absmax_batch.argtypes = [vp, vp, vp]
+        L.mpq_quant_error_batch_workspace_bytes.restype = sz
+        L.mpq_quant_error_batch_workspace_bytes.argtypes = [vp, ci, ci, ci]
+        L.mpq_quant_error_batch.argtypes = [vp, vp, ci, ci, ci, vp, sz, vp]
         L.mpq_noise_inject.argtypes = [vp, i64, i64, ci, vp, ci, C.c_float, C.c_uint64, C.c_uint64, vp, vp]
         L.mpq_noise_inject_sweep.argtypes = [vp, i64, i64, ci, vp, ci, ci, C.c_float, C.c_uint64, C.c_uint64, vp, i64, vp]
         L.mpq_fake_quant_scales.argtypes = [vp, i64, i64, ci, vp, vp, ci, vp, vp, vp]
@@ -251,6 +260,81 @@ def quant_error_noalloc(x, absmax, out, b_lo=2, b_hi=8, gran=PER_TENSOR):
     _check(lib().mpq_quant_error_noalloc(_ptr(x), rows, cols, gran, _ptr(absmax), b_lo, b_hi, _ptr(out),
                                          _stream()), "mpq_quant_error_noalloc")
     return out
+
+
+SWEEP_TENSOR_AND_ROW = 3
+
+
+class SweepTensor(C.Structure):
+    """mpq_sweep_tensor of include/mpq.h: a host struct of device pointers."""
+    _fields_ = [("x", C.c_void_p), ("rows", C.c_int64), ("cols", C.c_int64), ("absmax_row", C.c_void_p),
+                ("absmax_tensor", C.c_void_p), ("sse_tensor", C.c_void_p), ("sse_row", C.c_void_p)]
+
+
+class SweepPlan:
+    """The plan of the batched sweep calls for a fixed set of 2-D fp32 device tensors: allocates
+    the result buffers (absmax_row / absmax_tensor / sse_tensor / sse_row per tensor), has the
+    library build the plan in host memory and uploads the bytes.  Keeps everything alive."""
+
+    def __init__(self, tensors, b_lo=2, b_hi=8):
+        torch = _torch()
+        self.tensors = [_dev2d(t, torch.float32) for t in tensors]
+        self.b_lo, self.b_hi = b_lo, b_hi
+        nb = b_hi - b_lo + 1
+        dev = self.tensors[0].device
+        f32, f64 = torch.float32, torch.float64
+        n = len(self.tensors)
+        rows = [t.shape[0] for t in self.tensors]
+        # one buffer per kind, cut into per-tensor views: results of a sweep read back in one copy
+        self.absmax_row_all = torch.empty(sum(rows), dtype=f32, device=dev)
+        self.absmax_tensor_all = torch.empty(n, dtype=f32, device=dev)
+        self.sse_tensor_all = torch.empty((n, nb), dtype=f64, device=dev)
+        self.sse_row_all = torch.empty((sum(rows), nb), dtype=f64, device=dev)
+        self.absmax_row, self.absmax_tensor, self.sse_tensor, self.sse_row = [], [], [], []
+        r0 = 0
+        for i, r in enumerate(rows):
+            self.absmax_row.append(self.absmax_row_all[r0:r0 + r])
+            self.absmax_tensor.append(self.absmax_tensor_all[i:i + 1])
+            self.sse_tensor.append(self.sse_tensor_all[i:i + 1])
+            self.sse_row.append(self.sse_row_all[r0:r0 + r])
+            r0 += r
+        self.desc = (SweepTensor * n)()
+        for i, t in enumerate(self.tensors):
+            self.desc[i] = SweepTensor(t.data_ptr(), t.shape[0], t.shape[1], self.absmax_row[i].data_ptr(),
+                                       self.absmax_tensor[i].data_ptr(), self.sse_tensor[i].data_ptr(),
+                                       self.sse_row[i].data_ptr())
+        nbytes = int(lib().mpq_sweep_plan_bytes(self.desc, n))
+        self.host = (C.c_uint64 * ((max(nbytes, 8) + 7) // 8))()
+        _check(lib().mpq_sweep_plan_build(self.desc, n, self.host, C.sizeof(self.host)), "mpq_sweep_plan_build")
+        self.nbytes = nbytes
+        self.dev = torch.frombuffer(self.host, dtype=torch.uint8).cuda()   # the caller uploads the plan
+        self.ws = Workspace()
+
+
+def sweep_plan_bytes(plan: "SweepPlan") -> int:
+    return plan.nbytes
+
+
+def sweep_plan_build(tensors, b_lo=2, b_hi=8) -> "SweepPlan":
+    return SweepPlan(tensors, b_lo, b_hi)
+
+
+def calibrate_absmax_batch(plan: "SweepPlan"):
+    """Row maxima and tensor maxima of every tensor of the plan; results in plan.absmax_row / absmax_tensor."""
+    _check(lib().mpq_calibrate_absmax_batch(plan.host, plan.dev.data_ptr(), _stream()), "mpq_calibrate_absmax_batch")
+    return plan
+
+
+def quant_error_batch_workspace_bytes(plan: "SweepPlan", gran=PER_TENSOR) -> int:
+    return int(lib().mpq_quant_error_batch_workspace_bytes(plan.host, gran, plan.b_lo, plan.b_hi))
+
+
+def quant_error_batch(plan: "SweepPlan", gran=PER_TENSOR):
+    """Eq. 2's sums of every tensor of the plan (results in plan.sse_tensor / plan.sse_row)."""
+    wp, wn = plan.ws.get(quant_error_batch_workspace_bytes(plan, gran))
+    _check(lib().mpq_quant_error_batch(plan.host, plan.dev.data_ptr(), gran, plan.b_lo, plan.b_hi, wp, wn, _stream()),
+           "mpq_quant_error_batch")
+    return plan
 
 
 def noise_inject(x, absmax, bits, lam, seed, stream_id, gran=PER_TENSOR, out=None):

@@ -329,3 +329,53 @@ def test_python_errors_carry_the_message():
     with pytest.raises(mpq.MpqError) as e:
         mpq._check(mpq.ERR_BITS, "mpq_fake_quant")
     assert "bit-width" in str(e.value) and e.value.status == mpq.ERR_BITS
+
+
+def _sweep_desc(x=0x10000, rows=8, cols=64, am_r=0x20000, am_t=0x30000, st=0x40000, sr=0x50000):
+    return mpq.SweepTensor(x, rows, cols, am_r, am_t, st, sr)
+
+
+def test_sweep_plan_build_validation_and_layout():
+    """Pure host code: runs with or without a GPU (the pointers are never dereferenced)."""
+    L = mpq.lib()
+    arr = (mpq.SweepTensor * 2)(_sweep_desc(), _sweep_desc(rows=100, cols=4096))
+    n = L.mpq_sweep_plan_bytes(arr, 2)
+    assert n > 0 and L.mpq_sweep_plan_bytes(arr, 0) == 0 and L.mpq_sweep_plan_bytes(None, 2) == 0
+    buf = (C.c_uint64 * ((n + 7) // 8))()
+    assert L.mpq_sweep_plan_build(arr, 2, buf, n) == mpq.OK
+    assert L.mpq_sweep_plan_build(arr, 2, buf, n - 1) == mpq.ERR_WORKSPACE
+    assert L.mpq_sweep_plan_build(None, 2, buf, n) == mpq.ERR_NULL
+    assert L.mpq_sweep_plan_build(arr, 2, None, n) == mpq.ERR_NULL
+    assert L.mpq_sweep_plan_build(arr, 0, buf, n) == mpq.ERR_SHAPE
+    # per-tensor workspace: one partial per 64 K-element chunk and bit-width (1 + 7 chunks here)
+    assert L.mpq_quant_error_batch_workspace_bytes(buf, mpq.PER_TENSOR, 2, 8) == (1 + 7) * 7 * 8
+    assert L.mpq_quant_error_batch_workspace_bytes(buf, mpq.PER_ROW, 2, 8) == 0
+    assert L.mpq_quant_error_batch_workspace_bytes(buf, mpq.SWEEP_TENSOR_AND_ROW, 2, 8) > 0
+    assert L.mpq_quant_error_batch_workspace_bytes(buf, mpq.PER_TENSOR, 1, 8) == 0
+    for bad, want in ((_sweep_desc(x=0), mpq.ERR_NULL), (_sweep_desc(x=0x10004), mpq.ERR_ALIGN),
+                      (_sweep_desc(cols=66), mpq.ERR_SHAPE), (_sweep_desc(rows=0), mpq.ERR_SHAPE),
+                      (_sweep_desc(cols=16388), mpq.ERR_SHAPE), (_sweep_desc(am_r=0), mpq.ERR_NULL),
+                      (_sweep_desc(am_t=0), mpq.ERR_NULL), (_sweep_desc(st=0x40004), mpq.ERR_ALIGN)):
+        one = (mpq.SweepTensor * 1)(bad)
+        assert L.mpq_sweep_plan_build(one, 1, buf, n) == want
+
+
+@needs_no_gpu
+def test_sweep_batch_call_validation():
+    L = mpq.lib()
+    arr = (mpq.SweepTensor * 1)(_sweep_desc())
+    n = L.mpq_sweep_plan_bytes(arr, 1)
+    buf = (C.c_uint64 * ((n + 7) // 8))()
+    assert L.mpq_sweep_plan_build(arr, 1, buf, n) == mpq.OK
+    junk = (C.c_uint64 * 8)()
+    assert L.mpq_calibrate_absmax_batch(junk, FAKE16, None) == mpq.ERR_SHAPE      # not a plan
+    assert L.mpq_calibrate_absmax_batch(buf, None, None) == mpq.ERR_NULL
+    assert L.mpq_calibrate_absmax_batch(buf, C.c_void_p(0x10004), None) == mpq.ERR_ALIGN
+    f = L.mpq_quant_error_batch
+    assert f(buf, FAKE16, mpq.PER_COL, 2, 8, FAKE16, 1 << 20, None) == mpq.ERR_GRAN
+    assert f(buf, FAKE16, mpq.PER_TENSOR, 2, 9, FAKE16, 1 << 20, None) == mpq.ERR_BITS
+    assert f(buf, FAKE16, mpq.PER_TENSOR, 2, 8, None, 0, None) == mpq.ERR_WORKSPACE
+    assert f(buf, FAKE16, mpq.PER_TENSOR, 2, 8, FAKE16, 8, None) == mpq.ERR_WORKSPACE
+    nost = (mpq.SweepTensor * 1)(_sweep_desc(st=0))
+    assert L.mpq_sweep_plan_build(nost, 1, buf, n) == mpq.OK
+    assert f(buf, FAKE16, mpq.PER_TENSOR, 2, 8, FAKE16, 1 << 20, None) == mpq.ERR_NULL
