@@ -1,9 +1,18 @@
 #!/usr/bin/env python3
 """Benchmark of the libmpq hot path on one MI355X.
 
-One "step" = one pass of the whole hot path over one batch of synthetic input of the chosen
-workload.  Default workload (`--workload cfg2`): configuration 2, the ResNet-50-shaped
-conv-as-GEMM stack (8 layers at batch 32).  Per layer a step runs, through the C ABI:
+Default (`--workload headline`): both halves of the metric on their own workloads, in one JSON line.
+  sweep  configuration 4, the sensitivity sweep over the 96 BERT-large weight tensors (302 M
+         elements, 1.208 GB): a step = max calibration per output channel and per tensor, then the
+         error sums of b = 2..8 per tensor and per output channel, all through the batched calls
+         (5 launches).  `value` = 12 bytes per element (three reads of 4 bytes) / time.  The seven
+         noise levels per tensor are timed separately and reported separately.
+  gemm   mpq_qgemm on every configured GEMM shape (configurations 2, 3, 5; int8 and packed int4
+         weights), cold operands: TOP/s, fraction of the int8 matrix peak and of the shape's own
+         roofline.
+  cfg2   the whole per-layer path of configuration 2 (below), as a block of the same line.
+`--workload cfg2`: configuration 2, the ResNet-50-shaped conv-as-GEMM stack (8 layers at batch 32).
+Per layer a step runs, through the C ABI:
     absmax(A) per tensor, absmax(W) per output channel            (calibration, Sec. 3.1)
     quant_error(A) and quant_error(W), b = 2..8 in one read each  (Eq. 2)
     noise_inject(W) at the layer's weight bit-width               (Eq. 3-5)
@@ -12,10 +21,10 @@ conv-as-GEMM stack (8 layers at batch 32).  Per layer a step runs, through the C
     sse_pair(Y, Y_ref)                                            (candidate score)
 Other workloads (the parity-test configurations, measured with the same machinery):
     cfg3  BERT-base encoder linears at M = 12288, same per-layer path, per-tensor scales
-    cfg4  sensitivity sweep over the 96 BERT-large weight tensors: absmax + quant_error per tensor
-          and per output channel, noise at every b = 2..8 from one call per tensor; the tensors are
-          independent and are dealt to 4 streams (cfg4-1stream: one after the other;
-          cfg4-unfused: one call per granularity and per noise level, one stream)
+    cfg4  the sensitivity sweep with one call per tensor instead of the batched calls: absmax +
+          quant_error per tensor and per output channel, noise at every b = 2..8 from one call per
+          tensor; the tensors are independent and are dealt to 4 streams (cfg4-1stream: one after
+          the other; cfg4-unfused: one call per granularity and per noise level, one stream)
     cfg5  64 candidate bit configurations of a BERT-large FFN block at M = 16384, back to back;
           GELU and the calibration of its output in the first GEMM's epilogue, the output score in
           the second's
@@ -495,6 +504,242 @@ def workload_cfg5(torch, P, workloads, mode):
 
 
 # ------------------------------------------------------------------------------------------------
+# the default run: the metric's two halves on their own workloads
+def _timed_calls(torch, calls, reps):
+    """Average duration in microseconds of each call of `calls` (name -> function), `reps` launches
+    each, HIP events on the launch stream around every single call, the host kept ahead of the GPU
+    by a spin kernel."""
+    out = {}
+    for name, fn in calls.items():
+        fn()
+        torch.cuda.synchronize()
+        pairs = []
+        torch.cuda._sleep(3_000_000)
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            pairs.append((e0, e1))
+        torch.cuda.synchronize()
+        out[name] = sum(a.elapsed_time(b) for a, b in pairs) * 1e3 / reps
+    return out
+
+
+# HBM traffic per launch of the batched sweep kernels over configuration 4, bytes, from the rocprofv3
+# counter runs summarised in profiles/cfg4_batched_sweep_hbm_traffic.txt (FETCH_SIZE and WRITE_SIZE
+# scaled by what the same counters read for a plain device copy of known size in the same run).
+TRAFFIC_BYTES_PER_LAUNCH_CFG4 = {}
+
+
+def bench_sweep_cfg4(torch, mpq, workloads, steps, warmup):
+    host = [w for _, w in workloads.cfg4_tensors()]
+    tensors = [torch.from_numpy(w).cuda() for w in host]
+    n = sum(t.numel() for t in tensors)
+    plan = mpq.sweep_plan_build(tensors)
+
+    def step():
+        mpq.calibrate_absmax_batch(plan)
+        mpq.quant_error_batch(plan, mpq.PER_TENSOR)
+        mpq.quant_error_batch(plan, mpq.PER_ROW)
+
+    for _ in range(max(warmup, 1)):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    us = _timed_calls(torch, {
+        "calibrate_absmax_batch": lambda: mpq.calibrate_absmax_batch(plan),
+        "quant_error_batch_per_tensor": lambda: mpq.quant_error_batch(plan, mpq.PER_TENSOR),
+        "quant_error_batch_per_row": lambda: mpq.quant_error_batch(plan, mpq.PER_ROW),
+        "quant_error_batch_both_in_one_read": lambda: mpq.quant_error_batch(plan, mpq.SWEEP_TENSOR_AND_ROW),
+    }, steps)
+    gbs = {k: 4.0 * n / v / 1e3 for k, v in us.items()}
+    # the noise levels: one call per tensor, seven planes each (4 bytes read + 28 written per element)
+    noisy = {}
+    for t in tensors:
+        if tuple(t.shape) not in noisy:
+            noisy[tuple(t.shape)] = torch.empty((7,) + tuple(t.shape), dtype=torch.float32, device=t.device)
+
+    def noise_step():
+        for i, t in enumerate(tensors):
+            mpq.noise_inject_sweep(t, plan.absmax_row[i], 2, 8, LAMBDA, 2302, i, mpq.PER_ROW, out=noisy[tuple(t.shape)])
+
+    noise_step()
+    torch.cuda.synchronize()
+    k_noise = max(1, min(steps, 5))
+    t0 = time.perf_counter()
+    for _ in range(k_noise):
+        noise_step()
+    torch.cuda.synchronize()
+    noise_ms = (time.perf_counter() - t0) * 1e3 / k_noise
+    slow = max(("quant_error_batch_per_tensor", "quant_error_batch_per_row"), key=lambda k: us[k])
+    return {
+        "tensors": len(tensors), "elements": n, "bytes_per_step": 12 * n, "launches_per_step": 5,
+        "ms_per_step": ms, "gbs": 12.0 * n / ms / 1e6, "frac_of_hbm_peak": 12.0 * n / ms / 1e6 / HBM_PEAK_GBS,
+        "call_us": {k: round(v, 2) for k, v in us.items()},
+        "call_gbs_at_4_bytes_per_element": {k: round(v, 1) for k, v in gbs.items()},
+        "call_frac_of_hbm_peak": {k: round(v / HBM_PEAK_GBS, 4) for k, v in gbs.items()},
+        "both_in_one_read_alu_view": {
+            "lane_ops_per_element": 57,
+            "t_lane_ops_per_s": round(57.0 * n / us["quant_error_batch_both_in_one_read"] / 1e6, 2),
+            "frac_of_alu_peak": round(57.0 * n / us["quant_error_batch_both_in_one_read"] / 1e6 / ALU_PEAK_TLANEOPS, 4)},
+        "noise_7_levels": {"ms_per_sweep": noise_ms, "bytes_per_sweep": 32 * n, "gbs": 32.0 * n / noise_ms / 1e6,
+                           "frac_of_hbm_peak": 32.0 * n / noise_ms / 1e6 / HBM_PEAK_GBS, "launches": len(tensors)},
+        "roofline": {"bound": "hbm", "achieved": gbs[slow], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": gbs[slow] / HBM_PEAK_GBS, "traffic": TRAFFIC_BYTES_PER_LAUNCH_CFG4.get(slow),
+                     "kernel": slow + " (b = 2..8, all 96 tensors in one launch + a finishing launch)",
+                     "algorithmic_per_launch": 4.0 * n, "avg_launch_us": us[slow], "bar": 0.70,
+                     "alu_view": {"lane_ops_per_element": 29, "achieved": 29.0 * n / us[slow] / 1e6,
+                                  "peak": ALU_PEAK_TLANEOPS, "unit": "T lane-op/s",
+                                  "frac": 29.0 * n / us[slow] / 1e6 / ALU_PEAK_TLANEOPS}},
+    }, host
+
+
+def gemm_shape_rows(workloads, reps=30, warmup=4):
+    from paper_2302_01382_amd import latency as lat
+    rows = []
+    for cfg, shapes in (("cfg2", workloads.CFG2), ("cfg3", workloads.CFG3), ("cfg5", workloads.CFG5)):
+        for g in shapes:
+            for st in (8, 4):
+                us = lat.time_qgemm(g.M, g.K, g.N, st, reps=reps, warmup=warmup)
+                ops = 2.0 * g.M * g.N * g.K
+                nbytes = g.M * g.K + g.N * g.K * st // 8 + 4.0 * g.M * g.N
+                tops = ops / us / 1e6
+                roof_tops = min(INT8_PEAK_TOPS, ops / nbytes * HBM_PEAK_GBS / 1e3)
+                rows.append({"shape": "%s.%s" % (cfg, g.name), "M": g.M, "K": g.K, "N": g.N, "w_storage_bits": st,
+                             "us": round(us, 2), "tops": round(tops, 1), "frac_of_int8_mfma_peak": round(tops / INT8_PEAK_TOPS, 4),
+                             "roofline_tops": round(roof_tops, 1), "frac_of_own_roofline": round(tops / roof_tops, 4),
+                             "bound": "mfma" if roof_tops >= INT8_PEAK_TOPS else "hbm"})
+    return rows
+
+
+def bench_gemm_block(torch, mpq, workloads, peaks):
+    rows = gemm_shape_rows(workloads)
+    for r in rows:
+        r["frac_of_measured_mfma_rate_random_bytes"] = round(r["tops"] / peaks["int8_mfma_tops_random_bytes"], 4)
+    long_k = [r for r in rows if r["K"] >= 2048]
+    best = max(rows, key=lambda r: r["tops"])
+    ops = sum(2.0 * r["M"] * r["N"] * r["K"] for r in rows)
+    us = sum(r["us"] for r in rows)
+    ops_k = sum(2.0 * r["M"] * r["N"] * r["K"] for r in long_k)
+    us_k = sum(r["us"] for r in long_k)
+    return {
+        "operands": "uniformly random int8 / nibbles, rotated through more buffers than the 256 MB memory-side cache holds; "
+                    "per-output-channel scales, fp32 output",
+        "tops_all_shapes": ops / us / 1e6, "tops_k_ge_2048_shapes": ops_k / us_k / 1e6,
+        "frac_of_int8_mfma_peak_k_ge_2048_shapes": ops_k / us_k / 1e6 / INT8_PEAK_TOPS,
+        "w4_not_slower_than_w8_within_2_percent": all(b["us"] <= 1.02 * a["us"] for a, b in zip(rows[0::2], rows[1::2])),
+        "shapes": rows,
+        "roofline": {"bound": "mfma", "achieved": best["tops"], "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
+                     "frac": best["tops"] / INT8_PEAK_TOPS, "traffic": None, "bar": 0.60,
+                     "kernel": "qgemm %s W%d (%d x %d x %d)" % (best["shape"], best["w_storage_bits"], best["M"], best["K"], best["N"]),
+                     "algorithmic_per_launch": 2.0 * best["M"] * best["N"] * best["K"], "avg_launch_us": best["us"],
+                     "frac_of_measured_mfma_rate_random_bytes": best["tops"] / peaks["int8_mfma_tops_random_bytes"]},
+    }
+
+
+def _cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline_headline(workloads, host_tensors):
+    """The oracle as it stands, on the host cores of this machine.  Sweep half: the same three passes
+    (row + tensor maxima, error sums per tensor, error sums per row) at full tensor size, on one
+    thread over the first 2 layers (8 tensors) and on all cores over the first 12 layers (48 tensors;
+    one tensor per task -- the oracle itself is single threaded, ctypes releases the interpreter
+    lock).  GEMM half: the oracle's triple loop on the first 256 rows of configuration 5's second
+    GEMM (rows are independent), with the extrapolation to all 16384 rows labelled as such."""
+    import numpy as np
+    import oracle
+    oracle.lib()
+
+    def sweep_one(w):
+        t0 = time.perf_counter()
+        mr = oracle.absmax(w, oracle.PER_ROW)
+        mt = oracle.absmax(w)
+        oracle.quant_error(w, mt)
+        oracle.quant_error(w, mr, gran=oracle.PER_ROW)
+        return time.perf_counter() - t0
+
+    one = host_tensors[:8]
+    t0 = time.perf_counter()
+    for w in one:
+        sweep_one(w)
+    t_one = time.perf_counter() - t0
+    gbs_one = 12.0 * sum(w.size for w in one) / t_one / 1e9
+    cores = max(1, len(os.sched_getaffinity(0)))
+    many = host_tensors[:48]
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(cores) as ex:
+        busy = sum(ex.map(sweep_one, many))
+    t_all = time.perf_counter() - t0
+    gbs_all = 12.0 * sum(w.size for w in many) / t_all / 1e9
+    g = workloads.CFG5[1]
+    r = np.random.Generator(np.random.PCG64(5))
+    a = r.integers(-127, 128, (256, g.K), dtype=np.int8)
+    w = r.integers(-127, 128, (g.N, g.K), dtype=np.int8)
+    t0 = time.perf_counter()
+    oracle.qgemm(a, w, np.ones(1, np.float32), np.ones(g.N, np.float32), 8, oracle.PER_ROW)
+    t_g = time.perf_counter() - t0
+    return {
+        "value": gbs_all, "unit": "GB/s", "cores": cores, "kind": "oracle", "cpu": _cpu_model(),
+        "sample": "configuration 4 sweep (row + tensor maxima, error sums b = 2..8 per tensor and per row; 12 bytes per "
+                  "element) at full tensor size: all cores on the first 48 of the 96 tensors, %.1f s wall, %.1f s "
+                  "summed over threads; one thread on the first 8 tensors, %.1f s" % (t_all, busy, t_one),
+        "value_one_thread": gbs_one,
+        "gemm": {"sample": "oracle triple loop on the first 256 of the 16384 rows of cfg5.ffn2 (K = 4096, N = 1024), one thread",
+                 "seconds_measured": t_g, "tops_measured": 2.0 * 256 * g.K * g.N / t_g / 1e12,
+                 "seconds_full_M_extrapolated": t_g * g.M / 256, "cores": 1},
+    }
+
+
+def run_headline(torch, mpq, workloads, args):
+    peaks = measured_peaks(torch, mpq)
+    sweep, host_tensors = bench_sweep_cfg4(torch, mpq, workloads, args.steps, args.warmup)
+    torch.cuda.empty_cache()
+    gemm = bench_gemm_block(torch, mpq, workloads, peaks)
+    torch.cuda.empty_cache()
+    # the per-layer path of configuration 2 as a third block
+    step, snapshot, nbytes, ops, label, layers = workload_layers(torch, mpq, workloads, "cfg2")
+    k2 = max(1, min(args.steps, 10))
+    m = measure(torch, step, snapshot, k2, min(args.warmup, 2))
+    probe_ms = m["probe"].totals_ms()
+    cfg2 = {"workload": label, "steps": k2, "ms_per_step": m["ms_per_step"], "gbs": nbytes / (m["ms_per_step"] * 1e-3) / 1e9,
+            "step_algorithmic_bytes": nbytes, "step_gemm_ops": ops, "launch": m["launch"], "qgemm": gemm_summary(m),
+            "timed_call_ms_probe_step": {k: round(v, 4) for k, v in probe_ms.items()},
+            "timed_call_gbs_probe_step": {k: round(m["probe"].bytes[k] / (v * 1e-3) / 1e9, 1) for k, v in probe_ms.items()},
+            "roofline_of_dominant_call": roofline_of(m, TRAFFIC_KIB_PER_LAUNCH_CFG2)}
+    del layers, step, snapshot
+    torch.cuda.empty_cache()
+    rooflines = [sweep.pop("roofline"), gemm.pop("roofline")]
+    head = min(rooflines, key=lambda r: r["frac"] / r["bar"])   # the kernel furthest below its bar
+    out = {
+        "metric": METRIC, "value": sweep["gbs"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": sweep["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 elementwise, int8 x int8 -> int32 GEMM", "data": "synthetic",
+        "config": {"workload": "cfg4 sensitivity sweep over the 96 BERT-large weight tensors (value, ms_per_step: max calibration "
+                               "per row and per tensor + error sums b = 2..8 per tensor and per row, batched calls, 12 bytes per "
+                               "element); qgemm on the 14 GEMM shapes of cfg2 / cfg3 / cfg5 (block `gemm`, headline shape "
+                               "cfg5.ffn2 16384 x 4096 x 1024); the cfg2 per-layer path (block `cfg2`)"},
+        "value_qgemm_tops_best_shape": rooflines[1]["achieved"],
+        "sweep": sweep, "gemm": gemm, "cfg2": cfg2, "roofline": head, "rooflines": rooflines, "measured_peaks": peaks,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline_headline(workloads, host_tensors)
+    print(json.dumps(out))
+
+
+# ------------------------------------------------------------------------------------------------
 def cpu_baseline(workloads, sample_rows):
     """The oracle, as it stands, over the configuration-2 path on a bounded sample: the first
     `sample_rows` activation rows of every layer with the full weight tensors.  Layers run on a
@@ -717,20 +962,7 @@ def run_gemm_shapes(torch, mpq, workloads, args):
     weights, per-output-channel scales, fp32 output), operands rotated through more than the
     memory-side cache holds: time per launch, TOP/s, fraction of the int8 matrix peak, and
     fraction of the shape's own roofline min(matrix peak, arithmetic intensity x HBM peak)."""
-    from paper_2302_01382_amd import latency as lat
-    rows = []
-    for cfg, shapes in (("cfg2", workloads.CFG2), ("cfg3", workloads.CFG3), ("cfg5", workloads.CFG5)):
-        for g in shapes:
-            for st in (8, 4):
-                us = lat.time_qgemm(g.M, g.K, g.N, st, reps=30, warmup=4)
-                ops = 2.0 * g.M * g.N * g.K
-                nbytes = g.M * g.K + g.N * g.K * st // 8 + 4.0 * g.M * g.N
-                tops = ops / us / 1e6
-                roof_tops = min(INT8_PEAK_TOPS, ops / nbytes * HBM_PEAK_GBS / 1e3)
-                rows.append({"shape": "%s.%s" % (cfg, g.name), "M": g.M, "K": g.K, "N": g.N, "w_storage_bits": st,
-                             "us": round(us, 2), "tops": round(tops, 1), "frac_of_int8_mfma_peak": round(tops / INT8_PEAK_TOPS, 4),
-                             "roofline_tops": round(roof_tops, 1), "frac_of_own_roofline": round(tops / roof_tops, 4),
-                             "bound": "mfma" if roof_tops >= INT8_PEAK_TOPS else "hbm"})
+    rows = gemm_shape_rows(workloads)
     best = max(rows, key=lambda r: r["tops"])
     peaks = measured_peaks(torch, mpq)
     for r in rows:
@@ -784,7 +1016,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", choices=["cfg2", "cfg3", "cfg4", "cfg4-1stream", "cfg4-unfused", "cfg5", "cfg5-twopass", "cfg5-unfused", "search", "latency", "hutchinson", "gemm"], default="cfg2")
+    ap.add_argument("--workload", choices=["cfg2", "cfg3", "cfg4", "cfg4-1stream", "cfg4-unfused", "cfg5", "cfg5-twopass", "cfg5-unfused", "search", "latency", "hutchinson", "gemm", "headline", "sweep"], default="headline")
     ap.add_argument("--cpu-sample-rows", type=int, default=2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--streams", type=int, default=4,
@@ -807,6 +1039,25 @@ def main():
     torch.cuda.set_device(0)
     mpq.lib()
 
+    if args.workload == "headline":
+        run_headline(torch, mpq, workloads, args)
+        return
+    if args.workload == "sweep":   # the sweep block of the default run alone (what the counter passes profile)
+        if args.calibrate_copy:
+            src = torch.empty(225792 * 256, dtype=torch.float32, device="cuda")   # 225792 KiB
+            dst = torch.empty_like(src)
+            for _ in range(3):
+                dst.copy_(src)
+            torch.cuda.synchronize()
+            del src, dst
+        sweep, _ = bench_sweep_cfg4(torch, mpq, workloads, args.steps, args.warmup)
+        roof = sweep.pop("roofline")
+        print(json.dumps({"metric": METRIC, "value": sweep["gbs"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+                          "warmup": args.warmup, "ms_per_step": sweep["ms_per_step"], "higher_is_better": True,
+                          "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+                          "config": {"workload": "cfg4 sensitivity sweep, batched calls (the sweep block of the default run)"},
+                          "sweep": sweep, "roofline": roof}))
+        return
     if args.workload == "search":
         run_search(torch, mpq, workloads, args)
         return
