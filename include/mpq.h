@@ -58,6 +58,12 @@ const char* mpq_strerror(int status);
 int mpq_last_hip_error(void);
 /* Library version, major*100 + minor. */
 int mpq_version(void);
+/* Optional.  Configures, on the caller's current device, every kernel variant of the quantized-layer
+ * calls that needs more than the default amount of on-chip memory (a per-kernel runtime attribute,
+ * not a stream operation).  Without it the first call that selects a variant does the same for
+ * that variant; code that records the calls into a HIP graph calls mpq_init() before the capture
+ * begins, or runs each call once eagerly first.  Thread safe, idempotent, allocates nothing. */
+int mpq_init(void);
 
 /* ---- Sec. 3.1, calibration step: m = max |x| --------------------------------------------
  * x          [rows x cols] fp32, any alignment (16-byte alignment enables 128-bit loads).
@@ -202,7 +208,12 @@ int mpq_noise_inject_sweep(const float* x, int64_t rows, int64_t cols, int gran,
  * K*127*127 must stay below 2^31 (K <= 133143), else MPQ_ERR_SHAPE.
  * 16-byte aligned a_q / w_q with K a multiple of 16 (32 for packed int4) take the fast path;
  * anything else is computed by a slower byte-wise loader with identical results.
- * No workspace is needed at present (ws may be NULL, the query returns 0). */
+ * Workspace: optional.  Shapes with a handful of output tiles and a long K (at most 64 tiles of
+ * 64 x 64, K >= 1024: any layer at inference batch 1) are cut along K when the caller passes
+ * the workspace the query asks for (16-byte aligned): partial int32 accumulators go to the
+ * workspace and are added by a second kernel -- integer sums, so acc_out and y_out are bit-identical
+ * to the unsplit product.  With ws == NULL (or too small) the same results are computed without
+ * the split, only slower on those shapes; the query returns 0 for shapes that are not split. */
 size_t mpq_qgemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int w_storage_bits);
 int mpq_qgemm(const int8_t* a_q, const void* w_q, int w_storage_bits, int64_t M, int64_t N,
               int64_t K, const float* a_scale, const float* w_scale, int w_gran, float* y_out,

@@ -156,10 +156,18 @@ extern "C" int mpq_calibrate_absmax(const float* x, int64_t rows, int64_t cols, 
   const int64_t n = rows * cols;
   const int64_t nseg = (cols + kSeg - 1) / kSeg;
   const bool direct = gran == MPQ_PER_ROW && nseg == 1 && !accumulate;
+  const bool a16 = aligned16(x);
+  const bool vec = a16 && (cols & 3) == 0;
+  // grid limits are part of the argument check: nothing is enqueued before they have passed
+  const int64_t row_blocks = (rows * nseg + kBlock / kWave - 1) / (kBlock / kWave);
+  const int64_t cols_per_block = vec ? kWave * 4 : kWave;
+  const int64_t col_gx = (cols + cols_per_block - 1) / cols_per_block;
+  if (gran == MPQ_PER_ROW && row_blocks > 0x7FFFFFFF) return MPQ_ERR_SHAPE;
+  if (gran == MPQ_PER_COL && col_gx > 0x7FFFFFFF) return MPQ_ERR_SHAPE;
+  if (gran != MPQ_PER_TENSOR && (nch + 255) / 256 > 0x7FFFFFFF) return MPQ_ERR_SHAPE;
   if (!accumulate && !direct && gran != MPQ_PER_TENSOR) {
     fill_u32<<<(unsigned)((nch + 255) / 256), 256, 0, st>>>(out, nch, 0u);
   }
-  const bool a16 = aligned16(x);
   if (gran == MPQ_PER_TENSOR) {
     const unsigned g = absmax_flat_grid(n, a16);
     float* partials = reinterpret_cast<float*>(ws);
@@ -167,20 +175,13 @@ extern "C" int mpq_calibrate_absmax(const float* x, int64_t rows, int64_t cols, 
     else absmax_flat<false><<<g, kBlock, 0, st>>>(x, n, partials);
     absmax_finish<<<1, kBlock, 0, st>>>(partials, (int)g, accumulate, absmax_out);
   } else if (gran == MPQ_PER_ROW) {
-    const int64_t items = rows * nseg;
-    const int64_t blocks = (items + kBlock / kWave - 1) / (kBlock / kWave);
-    if (blocks > 0x7FFFFFFF) return MPQ_ERR_SHAPE;
-    const bool vec = a16 && (cols & 3) == 0;
-    const unsigned g = (unsigned)blocks;
+    const unsigned g = (unsigned)row_blocks;
     if (vec && direct) absmax_rows<true, true><<<g, kBlock, 0, st>>>(x, rows, cols, nseg, out);
     else if (vec) absmax_rows<true, false><<<g, kBlock, 0, st>>>(x, rows, cols, nseg, out);
     else if (direct) absmax_rows<false, true><<<g, kBlock, 0, st>>>(x, rows, cols, nseg, out);
     else absmax_rows<false, false><<<g, kBlock, 0, st>>>(x, rows, cols, nseg, out);
   } else {
-    const bool vec = a16 && (cols & 3) == 0;
-    const int64_t cols_per_block = vec ? kWave * 4 : kWave;
-    const int64_t gx = (cols + cols_per_block - 1) / cols_per_block;
-    if (gx > 0x7FFFFFFF) return MPQ_ERR_SHAPE;
+    const int64_t gx = col_gx;
     // enough row chunks to give the chip ~8 blocks per CU, at least 16 rows per wave
     int64_t gy = ((int64_t)kNumCU * 8 + gx - 1) / gx;
     const int64_t max_gy = (rows + 4 * 16 - 1) / (4 * 16);

@@ -29,6 +29,15 @@ inline int launch_status() {
 int fake_quant_launch(const float* x, int64_t rows, int64_t cols, int gran, const float* absmax, int bits,
                       float* y_out, int8_t* codes_out, uint8_t* packed4_out, float* step_out, void* stream);
 
+// defined in qgemm.hip: the host-side argument checks of mpq_qgemm_act / mpq_qgemm_score, for callers
+// that must validate several layers before their first launch
+int check_qgemm_act_args(const int8_t* a_q, const void* w_q, int w_storage_bits, int64_t M, int64_t N, int64_t K,
+                         const float* a_scale, const float* w_scale, int w_gran, int act, const float* y_out,
+                         const float* absmax_out);
+int check_qgemm_score_args(const int8_t* a_q, const void* w_q, int w_storage_bits, int64_t M, int64_t N, int64_t K,
+                           const float* a_scale, const float* w_scale, int w_gran, const float* y_ref,
+                           const double* sse_out, const float* y_out, const void* ws, size_t ws_bytes);
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 inline bool mul_overflows(int64_t a, int64_t b) {

@@ -1,0 +1,12 @@
+// qgemm_t256.hip -- the fast path of mpq_qgemm (qgemm_dma.hpp) instantiated for one tile size; a
+// translation unit per tile size so that the sources compile side by side.
+#include "qgemm_dma.hpp"
+
+namespace mpq {
+
+int launch_dma_256(bool w4, const DmaArgs& a) {
+  return w4 ? launch_dma<256, 256, 4, 2, 2, true>(a.a_q, a.w_q, a.M, a.N, a.K, a.a_scale, a.w_scale, a.per_row, a.y_out, a.acc_out, a.st, a.epi, a.n_partials, a.split, a.k_per_split, a.prepare_only)
+            : launch_dma<256, 256, 4, 2, 2, false>(a.a_q, a.w_q, a.M, a.N, a.K, a.a_scale, a.w_scale, a.per_row, a.y_out, a.acc_out, a.st, a.epi, a.n_partials, a.split, a.k_per_split, a.prepare_only);
+}
+
+}  // namespace mpq

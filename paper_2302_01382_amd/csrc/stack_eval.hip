@@ -27,22 +27,29 @@ extern "C" int mpq_stack_evaluate(const mpq_stack_layer* layers, int n_layers, i
   if (n_layers <= 0 || M <= 0) return MPQ_ERR_SHAPE;
   if (act_bits < 2 || act_bits > 8) return MPQ_ERR_BITS;
   if (act < MPQ_ACT_NONE || act > MPQ_ACT_GELU) return MPQ_ERR_SHAPE;
-  // everything is checked before the first launch: a failing call leaves the device untouched
+  // Everything is checked before the first launch, with the very checks the per-layer calls apply,
+  // so that a failing call leaves the device untouched.
+  if (w_gran != MPQ_PER_TENSOR && w_gran != MPQ_PER_ROW) return MPQ_ERR_GRAN;
+  if (!ws || ws_bytes < mpq_stack_evaluate_workspace_bytes(layers, n_layers, M)) return MPQ_ERR_WORKSPACE;
   for (int l = 0; l < n_layers; ++l) {
     const mpq_stack_layer& L = layers[l];
     if (!L.w_q || !L.w_scale || !L.w_storage_bits || !L.a_codes) return MPQ_ERR_NULL;
     if (L.N <= 0 || L.K <= 0 || L.n_widths <= 0) return MPQ_ERR_SHAPE;
     if (width_index[l] < 0 || width_index[l] >= L.n_widths) return MPQ_ERR_SHAPE;
     const int w = width_index[l];
-    if (!L.w_q[w] || !L.w_scale[w]) return MPQ_ERR_NULL;
-    if (L.w_storage_bits[w] != 8 && L.w_storage_bits[w] != 4) return MPQ_ERR_BITS;
-    if (L.w_storage_bits[w] == 4 && (L.K & 1)) return MPQ_ERR_SHAPE;
+    int rc;
     if (l + 1 < n_layers) {
       if (!L.h) return MPQ_ERR_NULL;
       if (layers[l + 1].K != L.N) return MPQ_ERR_SHAPE;  // the layers must chain
+      rc = mpq::check_qgemm_act_args(L.a_codes, L.w_q[w], L.w_storage_bits[w], M, L.N, L.K, a_scale + l, L.w_scale[w],
+                                     w_gran, act, L.h, a_absmax + l + 1);
+    } else {
+      rc = mpq::check_qgemm_score_args(L.a_codes, L.w_q[w], L.w_storage_bits[w], M, L.N, L.K, a_scale + l, L.w_scale[w],
+                                       w_gran, y_ref, sse_out, nullptr, ws, ws_bytes);
     }
+    if (rc != MPQ_OK) return rc;
+    if (l > 0 && mpq::mul_overflows(M, L.K)) return MPQ_ERR_SHAPE;  // the quantizer's own shape check
   }
-  if (!ws || ws_bytes < mpq_stack_evaluate_workspace_bytes(layers, n_layers, M)) return MPQ_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   // the running maxima of the inputs of layers 1.. start at zero (the activation's output is what
   // they are taken of; layer 0's input was calibrated by the caller)

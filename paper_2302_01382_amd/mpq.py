@@ -18,7 +18,7 @@ ERR_NULL, ERR_SHAPE, ERR_BITS, ERR_ALIGN, ERR_WORKSPACE, ERR_GRAN, ERR_HIP, ERR_
 NOALLOC_SCRATCH_BYTES = 4 << 20
 
 EXPORTS = [
-    "mpq_strerror", "mpq_last_hip_error", "mpq_version", "mpq_calibrate_absmax_workspace_bytes",
+    "mpq_strerror", "mpq_last_hip_error", "mpq_version", "mpq_init", "mpq_calibrate_absmax_workspace_bytes",
     "mpq_calibrate_absmax",
     "mpq_scale_from_absmax", "mpq_fake_quant", "mpq_quant_error_workspace_bytes",
     "mpq_quant_error", "mpq_quant_error_noalloc", "mpq_noise_inject",
@@ -65,6 +65,8 @@ def lib():
         L.mpq_strerror.argtypes = [ci]
         L.mpq_last_hip_error.restype = ci
         L.mpq_version.restype = ci
+        L.mpq_init.restype = ci
+        L.mpq_init.argtypes = []
         L.mpq_calibrate_absmax_workspace_bytes.restype = sz
         L.mpq_calibrate_absmax_workspace_bytes.argtypes = [i64, i64, ci]
         L.mpq_calibrate_absmax.argtypes = [vp, i64, i64, ci, ci, vp, vp, sz, vp]
@@ -117,6 +119,11 @@ def lib():
             getattr(L, name)  # raises AttributeError if the library lacks a declared symbol
         _lib = L
     return _lib
+
+
+def init():
+    """Configures every kernel variant that needs it on the current device (see mpq_init)."""
+    _check(lib().mpq_init(), "mpq_init")
 
 
 def _check(status: int, call: str):
@@ -368,8 +375,9 @@ def qgemm_workspace_bytes(M, N, K, w_storage_bits=8) -> int:
 
 
 def qgemm(a_q, w_q, a_scale, w_scale, w_storage_bits=8, w_gran=PER_TENSOR, want_y=True,
-          want_acc=False, y=None, acc=None, ws: Workspace = None):
-    """Returns (Y fp32 [M,N] | None, acc int32 [M,N] | None)."""
+          want_acc=False, y=None, acc=None, ws: Workspace = None, use_workspace=True):
+    """Returns (Y fp32 [M,N] | None, acc int32 [M,N] | None).  use_workspace=False passes no
+    workspace: shapes the library would cut along K are then computed unsplit (same results)."""
     torch = _torch()
     a_q = _dev2d(a_q, torch.int8)
     M, K = a_q.shape
@@ -378,7 +386,7 @@ def qgemm(a_q, w_q, a_scale, w_scale, w_storage_bits=8, w_gran=PER_TENSOR, want_
         y = torch.empty((M, N), dtype=torch.float32, device=a_q.device)
     if want_acc and acc is None:
         acc = torch.empty((M, N), dtype=torch.int32, device=a_q.device)
-    wp, wn = (ws or _default_ws).get(qgemm_workspace_bytes(M, N, K, w_storage_bits))
+    wp, wn = (ws or _default_ws).get(qgemm_workspace_bytes(M, N, K, w_storage_bits)) if use_workspace else (None, 0)
     _check(lib().mpq_qgemm(_ptr(a_q), _ptr(w_q), w_storage_bits, M, N, K, _ptr(a_scale),
                            _ptr(w_scale), w_gran, _ptr(y), _ptr(acc), wp, wn, _stream()), "mpq_qgemm")
     return y, acc

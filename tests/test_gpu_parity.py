@@ -346,6 +346,42 @@ def test_qgemm_large_tiles_on_sampled_rows(mnk, wbits):
     np.testing.assert_allclose(host(y_t)[rows], y_to, rtol=RTOL_Y, atol=0)
 
 
+@pytest.mark.parametrize("mnk,wbits", [((200, 130, 4608), 8), ((200, 132, 4608), 4), ((49, 512, 4608), 8),
+                                        ((49, 512, 2048), 4), ((130, 70, 1040), 8), ((300, 200, 1056), 4),
+                                        ((70, 131, 2048), 8), ((1, 64, 16384), 8), ((64, 1000, 1024), 4),
+                                        ((500, 500, 1152), 8)])
+def test_qgemm_split_along_k_is_bit_identical(mnk, wbits):
+    """Few output tiles and a long K: with a workspace the library cuts K into ranges (ragged last
+    range, K not a multiple of the k tile or of the range count, packed int4, N not a multiple of
+    4) and adds the integer partial products.  Accumulators equal the oracle's bit for bit, Y to
+    1e-5, and both equal the unsplit run of the same call."""
+    M, N, K = mnk
+    assert mpq.qgemm_workspace_bytes(M, N, K, wbits) >= 2 * 4 * M * N       # this shape is split
+    q = 127 if wbits == 8 else 7
+    a, w = rand_codes((M, K), 127, 60), rand_codes((N, K), q, 61)
+    ws = w if wbits == 8 else oracle.pack4(w)
+    sa = np.array([0.02], np.float32)
+    sw = (np.random.Generator(np.random.PCG64(62)).random(N).astype(np.float32) + 0.5) * np.float32(1e-3)
+    y_o, acc_o = oracle.qgemm(a, ws, sa, sw, wbits, oracle.PER_ROW)
+    y, acc = mpq.qgemm(dev(a), dev(ws), dev(sa), dev(sw), wbits, mpq.PER_ROW, want_y=True, want_acc=True)
+    np.testing.assert_array_equal(host(acc), acc_o)
+    np.testing.assert_allclose(host(y), y_o, rtol=RTOL_Y, atol=0)
+    y1, acc1 = mpq.qgemm(dev(a), dev(ws), dev(sa), dev(sw), wbits, mpq.PER_ROW, want_y=True, want_acc=True,
+                         use_workspace=False)
+    np.testing.assert_array_equal(host(acc1), host(acc))
+    np.testing.assert_array_equal(host(y1), host(y))
+    # outputs and scales that are only 4-byte aligned take the scalar combine: same bits
+    y_buf = dev_misaligned(np.zeros((M, N), np.float32))
+    acc_buf = dev_misaligned(np.zeros((M, N), np.int32))
+    mpq.qgemm(dev(a), dev(ws), dev(sa), dev_misaligned(sw), wbits, mpq.PER_ROW, y=y_buf, acc=acc_buf)
+    np.testing.assert_array_equal(host(y_buf), host(y))
+    np.testing.assert_array_equal(host(acc_buf), acc_o)
+    # a single output, one scale for the tensor
+    y_t, none = mpq.qgemm(dev(a), dev(ws), dev(sa), dev(sw[:1].copy()), wbits, mpq.PER_TENSOR)
+    assert none is None
+    np.testing.assert_allclose(host(y_t), oracle.qgemm(a, ws, sa, sw[:1], wbits, oracle.PER_TENSOR)[0], rtol=RTOL_Y, atol=0)
+
+
 def test_qgemm_extreme_operands_and_single_outputs():
     a = np.full((130, 4608), -127, np.int8)
     w = np.full((70, 4608), 127, np.int8)
