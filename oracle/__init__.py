@@ -141,6 +141,17 @@ def eqe(sse: float, n: int, m: float) -> float:
     return float(lib().orc_eqe(C.c_double(sse), C.c_int64(n), C.c_float(m)))
 
 
+def eqe_channels(sse_ch, n: int, absmax_ch):
+    """Eq. 2 of a tensor quantized with one scale per channel, from its channels' error sums
+    [nch, nb] and maxima [nch]: float64 [nb]."""
+    s = np.ascontiguousarray(sse_ch, dtype=np.float64)
+    m = np.ascontiguousarray(absmax_ch, dtype=np.float32).ravel()
+    assert s.ndim == 2 and s.shape[0] == m.size
+    out = np.empty(s.shape[1], np.float64)
+    lib().orc_eqe_channels(_p(s), _p(m), C.c_int64(m.size), C.c_int(s.shape[1]), C.c_int64(n), _p(out))
+    return out
+
+
 def philox4x32_10(ctr, key):
     c = (C.c_uint32 * 4)(*[int(v) & 0xFFFFFFFF for v in ctr])
     k = (C.c_uint32 * 2)(*[int(v) & 0xFFFFFFFF for v in key])

@@ -15,7 +15,8 @@
 //                       (2^(b-1) - 1)-level variant: scale = m/qmax, inv = qmax/m.
 //   orc_fake_quant      Sec. 3.1 Eq. 1: round(clip(alpha x) * levels) / levels * gamma.
 //   orc_quant_error     Sec. 3.2.1 Eq. 2: the expectation inside E_QE, as a sum of squares.
-//   orc_eqe             Sec. 3.2.1 Eq. 2 itself.
+//   orc_eqe, orc_eqe_channels
+//                       Sec. 3.2.1 Eq. 2 itself (one scale per tensor; one scale per channel).
 //   orc_noise_inject    Sec. 3.2.2 Eq. 3-5: w_i + nu, nu Gaussian with spread tied to max|w_i|.
 //   orc_qgemm           Alg. 1 / Alg. 2 "Evaluate f(x, w)": one linear layer with both operands
 //                       quantized; integer contraction, floating-point rescale.
@@ -199,6 +200,19 @@ int orc_quant_error(const float* x, int64_t rows, int64_t cols, int gran, const 
 double orc_eqe(double sse, int64_t n, float absmax) {
   if (n <= 0 || !(absmax > 0.0f)) return 0.0;
   return std::sqrt(sse / (double)n) / (double)absmax;
+}
+
+// Eq. 2 for a tensor quantized with one scale per channel: the expectation runs over all n elements
+// of the tensor, so the channels' error sums add up, and max|x| of the tensor is the largest
+// channel maximum.  sse: [nch][nb] (b ascending), absmax: [nch]; out: [nb].
+void orc_eqe_channels(const double* sse, const float* absmax, int64_t nch, int nb, int64_t n, double* out) {
+  float m = 0.0f;
+  for (int64_t c = 0; c < nch; ++c) m = absmax[c] > m ? absmax[c] : m;
+  for (int b = 0; b < nb; ++b) {
+    double total = 0.0;
+    for (int64_t c = 0; c < nch; ++c) total += sse[c * nb + b];
+    out[b] = orc_eqe(total, n, m);
+  }
 }
 
 // ------------------------------------------------------------------------------------------
