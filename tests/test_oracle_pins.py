@@ -287,6 +287,28 @@ def test_eqe_is_normalised_rmse_and_matches_textbook_int8():
     assert oracle.eqe(0.0, 10, 0.0) == 0.0
 
 
+def test_eqe_with_one_scale_per_channel():
+    """Eq. 2 when every output channel has its own scale: the root of the mean squared error over ALL
+    elements, relative to the tensor's max|x| -- against numpy on the dequantized tensor, and reducing
+    to the per-tensor value when all channels are given the tensor's maximum."""
+    r = rng(12)
+    x = (r.standard_normal((24, 96)) * np.linspace(0.1, 3.0, 24)[:, None]).astype(np.float32)
+    mr = oracle.absmax(x, PER_ROW)
+    got = oracle.eqe_channels(oracle.quant_error(x, mr, gran=PER_ROW), x.size, mr)
+    for i, b in enumerate(range(2, 9)):
+        y, _, _ = oracle.fake_quant(x, mr, b, PER_ROW)
+        rmse = np.sqrt(np.mean((y.astype(np.float64) - x.astype(np.float64)) ** 2))
+        assert got[i] == pytest.approx(rmse / float(np.abs(x).max()), rel=1e-5)
+    mt = oracle.absmax(x)
+    same = np.full(24, mt[0], np.float32)
+    per_t = oracle.quant_error(x, mt)[0]
+    np.testing.assert_allclose(oracle.eqe_channels(oracle.quant_error(x, same, gran=PER_ROW), x.size, same),
+                               [oracle.eqe(s, x.size, float(mt[0])) for s in per_t], rtol=1e-12)
+    # finer scales can only help: per-channel E_QE <= per-tensor E_QE here (rows differ 30-fold in range)
+    assert np.all(got < [oracle.eqe(s, x.size, float(mt[0])) for s in per_t])
+    assert np.all(oracle.eqe_channels(np.zeros((3, 7)), 12, np.zeros(3, np.float32)) == 0.0)
+
+
 # ------------------------------------------------------------------- noise (Eq. 3-5) and its RNG
 def test_philox_published_known_answers():
     n = 0
