@@ -5,7 +5,7 @@
  * Search".  The calls below are the per-tensor operations its searches (Alg. 1 bisection, Alg. 2
  * greedy) and sensitivity metrics (Sec. 3.2) execute over and over: max calibration (Sec. 3.1),
  * the quantizer of Eq. 1, the error sum inside Eq. 2, the perturbation of Eq. 3-5, and the
- * quantized linear layer evaluated by "Evaluate f(x, w)".
+ * quantized linear layer that the evaluation step of both algorithms runs.
  *
  * Conventions common to every call
  *  - All data pointers are DEVICE pointers (HIP global memory) unless a comment says "host".
@@ -112,6 +112,16 @@ size_t mpq_quant_error_workspace_bytes(int64_t rows, int64_t cols, int gran, int
 int mpq_quant_error(const float* x, int64_t rows, int64_t cols, int gran, const float* absmax,
                     int b_lo, int b_hi, double* sse_out, void* ws, size_t ws_bytes, void* stream);
 
+/* Eq. 2 itself, from the sums above (HOST functions on HOST values; the caller has read the sums back):
+ *   mpq_eqe          E_QE = sqrt(sse / n) / absmax, n the number of elements the sum ran over;
+ *                    0 when absmax == 0 (an all-zero tensor has no error) or n <= 0.
+ *   mpq_eqe_channels the same for a tensor quantized with one scale per channel, from its channels'
+ *                    sums sse[nch][nb] (what mpq_quant_error writes per row / column) and maxima
+ *                    absmax[nch]: the expectation of Eq. 2 runs over all n elements of the tensor, so
+ *                    eqe_out[b] = sqrt(sum_c sse[c][b] / n) / max_c absmax[c], b < nb. */
+double mpq_eqe(double sse, int64_t n, double absmax);
+int mpq_eqe_channels(const double* sse, const float* absmax, int64_t nch, int nb, int64_t n, double* eqe_out);
+
 /* mpq_quant_error for callers that cannot allocate device memory and have no workspace to hand
  * over: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
  * arguments (minus the workspace), same kernels and bit-for-bit the same results as
@@ -197,7 +207,7 @@ int mpq_noise_inject_sweep(const float* x, int64_t rows, int64_t cols, int gran,
                            int b_lo, int b_hi, float lambda, uint64_t seed, uint64_t stream_id,
                            float* y_out, int64_t y_stride, void* stream);
 
-/* ---- "Evaluate f(x, w)" of Alg. 1 / Alg. 2: one quantized linear layer ------------------------
+/* ---- the evaluation step of Alg. 1 / Alg. 2: one quantized linear layer ------------------------
  * acc[m][n] = sum_k a_q[m][k] * w_q[n][k] (int32), y[m][n] = fl32(fl32(float(acc) * a_scale[0])
  *             * w_scale[n or 0]).
  * a_q        int8 [M x K], K contiguous.
@@ -219,14 +229,14 @@ int mpq_qgemm(const int8_t* a_q, const void* w_q, int w_storage_bits, int64_t M,
               int64_t K, const float* a_scale, const float* w_scale, int w_gran, float* y_out,
               int32_t* acc_out, void* ws, size_t ws_bytes, void* stream);
 
-/* ---- "save accuracy a" of Alg. 1 / Alg. 2, stand-in score: squared output error ---------------
+/* ---- the score kept by the evaluation step of Alg. 1 / Alg. 2, stand-in: squared output error -------
  * sse_out[0] = sum_i (y[i] - y_ref[i])^2 (double).  fp32 per-lane partials, fixed-order double
  * combine.  Dividing by n gives the candidate's output MSE. */
 size_t mpq_sse_pair_workspace_bytes(int64_t n);
 int mpq_sse_pair(const float* y, const float* y_ref, int64_t n, double* sse_out, void* ws,
                  size_t ws_bytes, void* stream);
 
-/* ---- the layer of mpq_qgemm with what follows it in "Evaluate f(x, w)" taken in its epilogue ----
+/* ---- the layer of mpq_qgemm with what follows it inside an evaluation taken in its epilogue ----
  * y_out = act(Y) with Y as mpq_qgemm defines it, act one of mpq_act:
  *   MPQ_ACT_RELU  max(Y, 0);   MPQ_ACT_GELU  Y * Phi(Y), Phi the standard normal distribution
  *   function, evaluated in fp32 from a fitted approximation of its tail: within 1e-5 relative of
@@ -283,8 +293,12 @@ int mpq_hutchinson_quad(const float* x, int64_t M, int64_t K, const float* v, in
  * (MPQ_ERR_SHAPE otherwise: draw the matrix and use the call above).  Same workspace query. */
 int mpq_hutchinson_quad_signs(const float* x, int64_t M, int64_t K, uint64_t seed, uint64_t stream_id,
                               int64_t P, double* quad_out, void* ws, size_t ws_bytes, void* stream);
+/* The estimate itself (HOST function on the P quadratic forms read back from the device):
+ * estimate_out[0] = (2 / rows) * mean_p quad[p], rows = M of the tensor the forms were taken of, and
+ * std_error_out[0] (nullable) = (2 / rows) * sample standard deviation of quad / sqrt(P), NaN for P = 1. */
+int mpq_hutchinson_trace(const double* quad, int64_t P, int64_t rows, double* estimate_out, double* std_error_out);
 
-/* ---- "Evaluate f(x, w) and save accuracy a" of Alg. 1 / Alg. 2 in one call -------------------
+/* ---- the evaluation step of Alg. 1 / Alg. 2 in one call -------------------
  * The layer of mpq_qgemm with the score of mpq_sse_pair taken in its epilogue:
  * sse_out[0] = sum_{m,n} (y[m][n] - y_ref[m][n])^2 (double), y exactly as mpq_qgemm defines it.
  * y_ref      fp32 [M x N], required.
@@ -323,7 +337,7 @@ int mpq_scale_grad(const float* x, int64_t rows, int64_t cols, int gran, const f
 int mpq_scale_sgd_step(float* inv, float* scale, const double* dinv, const double* dscale,
                        int64_t count, double lr, void* stream);
 
-/* ---- "Evaluate f(x, lw) and save accuracy a" for a whole stack of layers in one call ------------
+/* ---- the evaluation step of Alg. 1 / Alg. 2 for a whole stack of layers in one call ------------
  * The model f is n_layers linear layers with an activation between them.  Layer l has weights
  * [N_l x K_l] (K_{l+1} = N_l) quantized beforehand at each of its n_widths candidate widths; an
  * evaluation picks one width per layer (width_index[l], host array) and enqueues, per layer,
@@ -354,7 +368,7 @@ int mpq_stack_evaluate(const mpq_stack_layer* layers, int n_layers, int64_t M, c
 /* ---- Alg. 1 (bisection search) and Alg. 2 (greedy search): host code ---------------------------
  * Both decide which per-layer bit configuration to evaluate next and return the final one; they
  * launch nothing themselves.  All pointers here are HOST pointers.
- * eval       "Evaluate f(x, lw) and save accuracy a": called with bits[n_layers] (bits[l] = width
+ * eval       the evaluation step of Alg. 1 / Alg. 2: called with bits[n_layers] (bits[l] = width
  *            of layer l) and `user`; returns the accuracy a, which is compared with `target`
  *            (a >= target meets it).  Called from the calling thread, one call at a time.
  * order      the layer ids 0 .. n_layers-1 sorted by sensitivity in ascending order (a

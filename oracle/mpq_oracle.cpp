@@ -18,9 +18,9 @@
 //   orc_eqe, orc_eqe_channels
 //                       Sec. 3.2.1 Eq. 2 itself (one scale per tensor; one scale per channel).
 //   orc_noise_inject    Sec. 3.2.2 Eq. 3-5: w_i + nu, nu Gaussian with spread tied to max|w_i|.
-//   orc_qgemm           Alg. 1 / Alg. 2 "Evaluate f(x, w)": one linear layer with both operands
+//   orc_qgemm           Alg. 1 / Alg. 2, evaluation step: one linear layer with both operands
 //                       quantized; integer contraction, floating-point rescale.
-//   orc_sse_pair        Alg. 1 / Alg. 2 "save accuracy a": stand-in score, squared output error.
+//   orc_sse_pair        Alg. 1 / Alg. 2, the score the evaluation step keeps: stand-in, squared output error.
 //   orc_fake_quant_scales, orc_scale_grad, orc_scale_sgd_step
 //                       Sec. 3.1, adjustment step: Eq. 1 with its two scales as free parameters,
 //                       their straight-through gradients, one gradient-descent step on them.
@@ -367,7 +367,7 @@ int orc_qgemm(const int8_t* a_q, const void* w_q, int w_storage_bits, int64_t M,
   return ORC_OK;
 }
 
-// Activations a layer may be followed by inside "Evaluate f(x, w)": ReLU, or GELU(x) = x Phi(x)
+// Activations a layer may be followed by inside the evaluation step: ReLU, or GELU(x) = x Phi(x)
 // with the exact Gaussian distribution function, evaluated in double and rounded to fp32 once.
 // act: 0 none, 1 ReLU, 2 GELU.  In place.
 int orc_activation(float* y, int64_t n, int act) {

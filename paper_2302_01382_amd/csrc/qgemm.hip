@@ -1,4 +1,4 @@
-// qgemm.hip -- one quantized linear layer, the dense core of "Evaluate f(x, w)" in the paper's
+// qgemm.hip -- one quantized linear layer, the dense core of the evaluation step in the paper's
 // Alg. 1 / Alg. 2: acc[m][n] = sum_k A_q[m][k] * W_q[n][k] in int32 on the int8 matrix cores,
 // then Y = (float(acc) * s_A) * s_W[n].
 //

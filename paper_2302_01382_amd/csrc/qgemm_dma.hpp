@@ -1,4 +1,4 @@
-// qgemm_dma.hpp -- the fast path of the quantized linear layer ("Evaluate f(x, w)" of the paper's
+// qgemm_dma.hpp -- the fast path of the quantized linear layer (the evaluation step of the paper's
 // Alg. 1 / Alg. 2): the templated multi-stage LDS pipeline fed by direct global->LDS loads, shared by
 // the translation units that instantiate one tile size each (qgemm_t*.hip), and the epilogue
 // options shared with the generic kernel (qgemm.hip).

@@ -1,20 +1,24 @@
 // search.hip -- the two configuration searches of the paper, Alg. 1 (bisection) and Alg. 2
 // (greedy), as host code.  They decide which bit configuration to evaluate next; the evaluation
-// itself ("Evaluate f(x, lw) and save accuracy a") is the caller's callback, which on this
-// library's path is a chain of mpq_fake_quant / mpq_qgemm / mpq_qgemm_score launches followed by
-// one read-back of the score.  Nothing here touches the device.
+// itself (the evaluation step of both algorithms) is the caller's callback, which on this
+// library's path is mpq_stack_evaluate or a chain of mpq_fake_quant / mpq_qgemm_act /
+// mpq_qgemm_score launches followed by one read-back of the score.  Nothing here touches the device.
+//
+// Both searches only ever lower a PREFIX of the sensitivity order (bisection) or single layers of
+// it (greedy), so the state is kept in those terms: the committed configuration, and for the
+// bisection the interval [lo, hi) of prefix lengths still in question.
 //
 // Readings of the printed algorithms (they leave these open):
 //  - bit widths are visited in the order the caller lists them (the text wants the highest
-//    quantized precision first, so callers pass them in descending order); the working
+//    quantized precision first, so callers pass them in descending order); the committed
 //    configuration starts at the largest listed width;
-//  - the threshold arithmetic of Alg. 1 is integer arithmetic with floor division, and "until thr
-//    is not changing" compares the threshold after the update with the one before it.
-//    Consequences of that arithmetic, kept as printed: the threshold never reaches the full list
-//    length, and when even a single layer fails the target the loop still ends at thr = 1.  With
-//    MPQ_SEARCH_ENSURE_TARGET the search falls back, in that last case, to the largest count it
-//    has seen meet the target (lowl), so that the returned configuration never relies on an
-//    evaluation that failed.
+//  - Alg. 1 moves its prefix length by integer halves of the distance to the bound on the side it
+//    is heading for, and stops at the first update that leaves the length where it was.
+//    Consequences of that arithmetic, kept as printed: the length never reaches the full list,
+//    and when the loop stops on an evaluation that missed the target the length stays on the
+//    count that failed.  With MPQ_SEARCH_ENSURE_TARGET the search falls back, in that case, to the
+//    largest length it has seen meet the target, so that the returned configuration never relies
+//    on an evaluation that failed.
 #include "mpq.h"
 
 #include <vector>
@@ -41,6 +45,29 @@ int widest(const int* bit_widths, int n_bits) {
   return m;
 }
 
+// One search in progress: the committed configuration and the callback that scores a trial.
+struct Trial {
+  const int* order;
+  int n_layers;
+  mpq_eval_fn eval;
+  void* user;
+  double target;
+  std::vector<int> committed, scratch;
+  int evals = 0;
+
+  // does the model meet the target with the first `count` layers of the order at `width` and
+  // every other layer as committed?
+  bool prefix_meets_target(int count, int width) {
+    scratch = committed;
+    for (int i = 0; i < count; ++i) scratch[(size_t)order[i]] = width;
+    ++evals;
+    return eval(scratch.data(), n_layers, user) >= target;
+  }
+  void commit_prefix(int count, int width) {
+    for (int i = 0; i < count; ++i) committed[(size_t)order[i]] = width;
+  }
+};
+
 }  // namespace
 
 extern "C" int mpq_search_bisection(const int* order, int n_layers, const int* bit_widths, int n_bits,
@@ -48,37 +75,33 @@ extern "C" int mpq_search_bisection(const int* order, int n_layers, const int* b
                                     int* config_out, int* n_evals_out) {
   const int rc = check_common(order, n_layers, bit_widths, n_bits, eval, config_out);
   if (rc != MPQ_OK) return rc;
-  const bool ensure = (flags & MPQ_SEARCH_ENSURE_TARGET) != 0;
-  std::vector<int> w((size_t)n_layers, widest(bit_widths, n_bits));  // working configuration
-  std::vector<int> lw((size_t)n_layers);
-  int len = n_layers;  // the layer list is always a prefix of `order`: ll = order[0 : len]
-  int evals = 0;
+  const bool fall_back = (flags & MPQ_SEARCH_ENSURE_TARGET) != 0;
+  Trial t{order, n_layers, eval, user, target, std::vector<int>((size_t)n_layers, widest(bit_widths, n_bits)), {}};
+  int candidates = n_layers;  // layers still eligible for a lower width: order[0 .. candidates)
   for (int bi = 0; bi < n_bits; ++bi) {
-    const int b = bit_widths[bi];
-    int thr = len / 2, upl = len, lowl = 0;
-    bool last_met = false;
+    const int width = bit_widths[bi];
+    int lo = 0, hi = candidates;  // lengths known to meet the target / known (or assumed) not to
+    int count = candidates / 2;
+    bool met;
     for (;;) {
-      lw = w;
-      for (int i = 0; i < thr; ++i) lw[(size_t)order[i]] = b;
-      const double a = eval(lw.data(), n_layers, user);
-      ++evals;
-      last_met = a >= target;
-      const int before = thr;
-      if (last_met) {
-        lowl = thr;
-        thr = thr + (upl - thr) / 2;
+      met = t.prefix_meets_target(count, width);
+      int next;
+      if (met) {
+        lo = count;
+        next = count + (hi - count) / 2;
       } else {
-        upl = thr;
-        thr = thr - (thr - lowl) / 2;
+        hi = count;
+        next = count - (count - lo) / 2;
       }
-      if (thr == before) break;
+      if (next == count) break;
+      count = next;
     }
-    if (ensure && !last_met) thr = lowl;
-    for (int i = 0; i < thr; ++i) w[(size_t)order[i]] = b;
-    len = thr;
+    if (!met && fall_back) count = lo;
+    t.commit_prefix(count, width);
+    candidates = count;
   }
-  for (int i = 0; i < n_layers; ++i) config_out[i] = w[(size_t)i];
-  if (n_evals_out) *n_evals_out = evals;
+  for (int i = 0; i < n_layers; ++i) config_out[i] = t.committed[(size_t)i];
+  if (n_evals_out) *n_evals_out = t.evals;
   return MPQ_OK;
 }
 
@@ -88,23 +111,22 @@ extern "C" int mpq_search_greedy(const int* order, int n_layers, const int* bit_
   (void)flags;  // every step of Alg. 2 that is kept was evaluated and met the target
   const int rc = check_common(order, n_layers, bit_widths, n_bits, eval, config_out);
   if (rc != MPQ_OK) return rc;
-  std::vector<int> w((size_t)n_layers, widest(bit_widths, n_bits));
-  std::vector<int> ll(order, order + n_layers), ql;
+  std::vector<int> config((size_t)n_layers, widest(bit_widths, n_bits));
+  std::vector<int> eligible(order, order + n_layers), still_eligible;  // in sensitivity order
   int evals = 0;
   for (int bi = 0; bi < n_bits; ++bi) {
-    const int b = bit_widths[bi];
-    ql.clear();
-    for (int l : ll) {
-      const int before = w[(size_t)l];
-      w[(size_t)l] = b;
-      const double a = eval(w.data(), n_layers, user);
+    const int width = bit_widths[bi];
+    still_eligible.clear();
+    for (int layer : eligible) {
+      const int keep = config[(size_t)layer];
+      config[(size_t)layer] = width;  // trial: this one layer lower, everything accepted so far stays
       ++evals;
-      if (a >= target) ql.push_back(l);
-      else w[(size_t)l] = before;  // and the layer is not a candidate for lower widths any more
+      if (eval(config.data(), n_layers, user) >= target) still_eligible.push_back(layer);
+      else config[(size_t)layer] = keep;  // rejected: back to its last accepted width, out of the lower rounds
     }
-    ll.swap(ql);
+    eligible.swap(still_eligible);
   }
-  for (int i = 0; i < n_layers; ++i) config_out[i] = w[(size_t)i];
+  for (int i = 0; i < n_layers; ++i) config_out[i] = config[(size_t)i];
   if (n_evals_out) *n_evals_out = evals;
   return MPQ_OK;
 }

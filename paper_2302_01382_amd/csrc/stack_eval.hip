@@ -1,4 +1,4 @@
-// stack_eval.hip -- "Evaluate f(x, lw) and save accuracy a" of Alg. 1 / Alg. 2 for a stack of
+// stack_eval.hip -- the evaluation step of Alg. 1 / Alg. 2 for a stack of
 // linear layers with an activation between them, as ONE host call: for every layer the quantizer
 // of its input (Eq. 1, the same kernel also leaves the step size), and the quantized layer with
 // the activation and the max calibration of the next input in its epilogue; the last layer's epilogue takes the score.  The

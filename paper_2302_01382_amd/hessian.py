@@ -8,12 +8,10 @@ Tr(H) = E_v[v' H v] needs only quadratic forms of X: with P random sign vectors 
 
 and with respect to the layer input X the same with W in place of X and N in place of M.  Both the
 probes (mpq_rademacher, or drawn inside mpq_hutchinson_quad_signs) and the quadratic forms
-(mpq_hutchinson_quad) are libmpq calls; only the
-mean and its standard error over P doubles are taken here.
+(mpq_hutchinson_quad) are libmpq calls, and so are the mean and its standard error over the P doubles
+read back (mpq_hutchinson_trace, host arithmetic).
 """
 from __future__ import annotations
-
-import math
 
 from . import mpq
 
@@ -28,8 +26,7 @@ def trace_linear_mse(x, probes: int = 32, seed: int = 0, stream_id: int = 0, ws:
     else:
         v = mpq.rademacher(seed, stream_id, probes, K, device=x.device)
         q = mpq.hutchinson_quad(x, v, ws=ws).cpu().numpy()
-    est = 2.0 / M * float(q.mean())
-    err = 2.0 / M * float(q.std(ddof=1)) / math.sqrt(probes) if probes > 1 else float("nan")
+    est, err = mpq.hutchinson_trace(q, M)   # mean and standard error: host arithmetic in the library
     return est, err
 
 

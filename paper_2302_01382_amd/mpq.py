@@ -22,6 +22,7 @@ EXPORTS = [
     "mpq_calibrate_absmax",
     "mpq_scale_from_absmax", "mpq_fake_quant", "mpq_quant_error_workspace_bytes",
     "mpq_quant_error", "mpq_quant_error_noalloc", "mpq_noise_inject",
+    "mpq_eqe", "mpq_eqe_channels", "mpq_hutchinson_trace",
     "mpq_sweep_plan_bytes", "mpq_sweep_plan_build", "mpq_calibrate_absmax_batch",
     "mpq_quant_error_batch_workspace_bytes", "mpq_quant_error_batch", "mpq_qgemm_workspace_bytes", "mpq_qgemm",
     "mpq_sse_pair_workspace_bytes", "mpq_sse_pair", "mpq_qgemm_score_workspace_bytes", "mpq_qgemm_score",
@@ -76,6 +77,10 @@ def lib():
         L.mpq_quant_error_workspace_bytes.argtypes = [i64, i64, ci, ci, ci]
         L.mpq_quant_error.argtypes = [vp, i64, i64, ci, vp, ci, ci, vp, vp, sz, vp]
         L.mpq_quant_error_noalloc.argtypes = [vp, i64, i64, ci, vp, ci, ci, vp, vp]
+        L.mpq_eqe.restype = C.c_double
+        L.mpq_eqe.argtypes = [C.c_double, i64, C.c_double]
+        L.mpq_eqe_channels.argtypes = [vp, vp, i64, ci, i64, vp]
+        L.mpq_hutchinson_trace.argtypes = [vp, i64, i64, vp, vp]
         L.mpq_sweep_plan_bytes.restype = sz
         L.mpq_sweep_plan_bytes.argtypes = [vp, ci]
         L.mpq_sweep_plan_build.argtypes = [vp, ci, vp, sz]
@@ -270,6 +275,34 @@ def quant_error_noalloc(x, absmax, out, b_lo=2, b_hi=8, gran=PER_TENSOR):
 
 
 SWEEP_TENSOR_AND_ROW = 3
+
+
+def eqe(sse: float, n: int, absmax: float) -> float:
+    """Eq. 2 from an error sum read back from the device (host arithmetic in the library)."""
+    return float(lib().mpq_eqe(float(sse), int(n), float(absmax)))
+
+
+def eqe_channels(sse_ch, n: int, absmax_ch):
+    """Eq. 2 of a tensor with one scale per channel, from host arrays sse_ch [nch, nb] (float64) and
+    absmax_ch [nch] (float32); returns a list of nb values."""
+    import numpy as np
+    s = np.ascontiguousarray(sse_ch, dtype=np.float64)
+    m = np.ascontiguousarray(absmax_ch, dtype=np.float32).ravel()
+    if s.ndim != 2 or s.shape[0] != m.size:
+        raise ValueError("sse_ch must be [nch, nb] with one absmax per channel")
+    out = (C.c_double * s.shape[1])()
+    _check(lib().mpq_eqe_channels(s.ctypes.data, m.ctypes.data, m.size, s.shape[1], int(n), out), "mpq_eqe_channels")
+    return list(out)
+
+
+def hutchinson_trace(quad, rows: int):
+    """(estimate, standard error) of the Hessian trace from the quadratic forms read back from the
+    device (host array of P float64) of a tensor with `rows` rows."""
+    import numpy as np
+    q = np.ascontiguousarray(quad, dtype=np.float64).ravel()
+    est, err = C.c_double(0.0), C.c_double(0.0)
+    _check(lib().mpq_hutchinson_trace(q.ctypes.data, q.size, int(rows), C.byref(est), C.byref(err)), "mpq_hutchinson_trace")
+    return est.value, err.value
 
 
 class SweepTensor(C.Structure):

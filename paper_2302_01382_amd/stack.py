@@ -1,4 +1,4 @@
-"""A stack of linear layers scored under a per-layer bit configuration: the "Evaluate f(x, lw)" of
+"""A stack of linear layers scored under a per-layer bit configuration: the evaluation step of
 the paper's searches (Alg. 1, Alg. 2) built from libmpq calls only.
 
 The model is y = W_L relu(... relu(W_1 x)): every layer's input is calibrated (max calibration,
@@ -74,6 +74,8 @@ class QuantStack:
         mpq.fake_quant(self.x, self.a_absmax[0], self.act_bits, want_y=False, codes=self.a_codes[0])
         mpq.scale_from_absmax(self.a_absmax[0], self.act_bits, out=self.a_scale[0])
         self.evaluations = 0
+        self.repeats = 0
+        self.scored: Dict[Tuple[int, ...], float] = {}
         self.use_graphs = use_graphs
         self.graphs = {}
         # the whole evaluation as one native call (mpq_stack_evaluate): the argument block is built once
@@ -95,6 +97,21 @@ class QuantStack:
         self.plan.evaluate([self.width_number[int(b)] for b in bits], self.sse, self.ws)
         self.evaluations += 1
         return 1.0 - float(self.sse.item()) / self.ref_norm2
+
+    def evaluate_once(self, bits: Sequence[int]) -> float:
+        """evaluate() behind a table of the configurations already scored: the searches re-ask for a
+        configuration they have seen whenever a trial changes nothing (the first width of the list
+        equals the starting width, a rejected trial is followed by one that restores it), and the
+        model is deterministic.  `evaluations` counts only the ones that ran on the device,
+        `repeats` the ones answered from the table."""
+        key = tuple(int(b) for b in bits)
+        hit = self.scored.get(key)
+        if hit is not None:
+            self.repeats += 1
+            return hit
+        a = self.evaluate(bits)
+        self.scored[key] = a
+        return a
 
     def evaluate_by_calls(self, bits: Sequence[int]) -> float:
         """The same evaluation issued call by call from Python (optionally as one HIP graph per
@@ -141,8 +158,7 @@ class QuantStack:
         for w in self.weights:
             am = mpq.calibrate_absmax(w, ws=self.ws)
             sse = mpq.quant_error(w, am, b_lo=b, b_hi=b, ws=self.ws)
-            m = float(am.item())
-            out.append(0.0 if m == 0.0 else (float(sse.item()) / w.numel()) ** 0.5 / m)
+            out.append(mpq.eqe(float(sse.item()), w.numel(), float(am.item())))
         return out
 
     def order_by(self, sensitivity: Sequence[float]) -> List[int]:
@@ -150,8 +166,8 @@ class QuantStack:
         return sorted(range(len(self.weights)), key=lambda l: (sensitivity[l], l))
 
     def bisection(self, order, target, ensure_target=True, evaluate=None):
-        return mpq.search_bisection(order, sorted(self.bit_widths, reverse=True), target, evaluate or self.evaluate,
+        return mpq.search_bisection(order, sorted(self.bit_widths, reverse=True), target, evaluate or self.evaluate_once,
                                     ensure_target)
 
     def greedy(self, order, target, evaluate=None):
-        return mpq.search_greedy(order, sorted(self.bit_widths, reverse=True), target, evaluate or self.evaluate)
+        return mpq.search_greedy(order, sorted(self.bit_widths, reverse=True), target, evaluate or self.evaluate_once)

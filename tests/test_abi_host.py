@@ -379,3 +379,48 @@ def test_sweep_batch_call_validation():
     nost = (mpq.SweepTensor * 1)(_sweep_desc(st=0))
     assert L.mpq_sweep_plan_build(nost, 1, buf, n) == mpq.OK
     assert f(buf, FAKE16, mpq.PER_TENSOR, 2, 8, FAKE16, 1 << 20, None) == mpq.ERR_NULL
+
+
+@needs_no_gpu
+def test_quantized_layer_calls_check_everything_before_their_first_launch():
+    """mpq_qgemm_act clears the running maximum with a small kernel before the product: every argument
+    error -- also the ones the shared dispatcher used to find only afterwards -- has to be reported
+    before that kernel could be enqueued.  (Without a GPU any launch attempt would surface as
+    MPQ_ERR_HIP instead of the argument error expected here.)"""
+    L = mpq.lib()
+    f = L.mpq_qgemm_act
+    ok = dict(a=FAKE16, w=FAKE16, bits=8, M=64, N=64, K=64, sa=FAKE16, sw=FAKE16, gran=mpq.PER_TENSOR, act=1,
+              y=FAKE16, am=FAKE16, acc=0)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(a["a"], a["w"], a["bits"], a["M"], a["N"], a["K"], a["sa"], a["sw"], a["gran"], a["act"], a["y"], a["am"],
+                 a["acc"], None)
+
+    assert call(y=C.c_void_p(0x10002)) == mpq.ERR_ALIGN            # 4-byte alignment of the output
+    assert call(am=C.c_void_p(0x10002)) == mpq.ERR_ALIGN
+    assert call(M=1 << 40, N=1 << 40) == mpq.ERR_SHAPE              # M * N overflows the element limit
+    assert call(M=70000 * 128 + 1, N=64) == mpq.ERR_SHAPE           # more row tiles than a grid holds
+    assert call(K=133144) == mpq.ERR_SHAPE
+    assert call(bits=4, K=63) == mpq.ERR_SHAPE
+    assert call(gran=mpq.PER_COL) == mpq.ERR_GRAN
+    assert call(act=7) == mpq.ERR_SHAPE
+    assert call(sa=None) == mpq.ERR_NULL
+    assert call(y=None, am=None) == mpq.ERR_NULL
+    # the stack evaluator applies the same per-layer checks to ALL layers before its clearing kernel
+    wq = (C.c_void_p * 1)(0x10000)
+    wsc = (C.c_void_p * 1)(0x20000)
+    st = (C.c_int * 1)(8)
+    good = mpq.StackLayer(64, 64, 1, C.cast(wq, C.POINTER(C.c_void_p)), C.cast(wsc, C.POINTER(C.c_void_p)),
+                          C.cast(st, C.POINTER(C.c_int)), 0x30000, 0x40000)
+    bad_k = mpq.StackLayer(64, 133144, 1, C.cast(wq, C.POINTER(C.c_void_p)), C.cast(wsc, C.POINTER(C.c_void_p)),
+                           C.cast(st, C.POINTER(C.c_int)), 0x30000, None)
+    misaligned_h = mpq.StackLayer(64, 64, 1, C.cast(wq, C.POINTER(C.c_void_p)), C.cast(wsc, C.POINTER(C.c_void_p)),
+                                  C.cast(st, C.POINTER(C.c_int)), 0x30000, 0x40002)
+    last = mpq.StackLayer(64, 64, 1, C.cast(wq, C.POINTER(C.c_void_p)), C.cast(wsc, C.POINTER(C.c_void_p)),
+                          C.cast(st, C.POINTER(C.c_int)), 0x30000, None)
+    idx = (C.c_int * 3)(0, 0, 0)
+    g = L.mpq_stack_evaluate
+    for layers, want in (((good, misaligned_h, last), mpq.ERR_ALIGN), ((good, good, bad_k), mpq.ERR_SHAPE)):
+        arr = (mpq.StackLayer * 3)(*layers)
+        assert g(arr, 3, 64, idx, 8, 1, mpq.PER_TENSOR, FAKE16, FAKE16, FAKE16, FAKE16, FAKE16, 1 << 20, None) == want
