@@ -391,6 +391,20 @@ int mpq_search_greedy(const int* order, int n_layers, const int* bit_widths, int
                       double target, int flags, mpq_eval_fn eval, void* user, int* config_out,
                       int* n_evals_out);
 
+/* ---- Experiments section, "Compute Latency Estimates" and Table 1: deployment estimates (HOST) ----
+ * The paper benchmarks the kernel of every layer shape at every precision (inference batch size 1)
+ * and combines the kernel latencies of a configuration's layers into a model latency; here the
+ * kernel is mpq_qgemm (timed by the caller with events) and the combination is the sum, layers of
+ * an inference pass running one after the other.
+ * mpq_latency_estimate: layer_us [n_layers x n_widths] (row-major) measured latencies of layer l
+ *   at its candidate precision number w; width_index[l] < n_widths the precision of layer l in the
+ *   configuration; total_us_out[0] = sum_l layer_us[l][width_index[l]].
+ * mpq_model_size_bytes: bytes_out[0] = sum_l parameters[l] * bits[l] / 8 (bits 1..64).
+ * All pointers are host pointers. */
+int mpq_latency_estimate(const double* layer_us, int n_layers, int n_widths, const int* width_index,
+                         double* total_us_out);
+int mpq_model_size_bytes(const int64_t* parameters, const int* bits, int n_layers, double* bytes_out);
+
 /* ---- measurement aid (not part of the method) --------------------------------------------------
  * Launches a kernel that does nothing but issue int8 matrix-core instructions (one workgroup of
  * eight waves per CU, 16 x iters instructions per wave) on operand registers filled once from

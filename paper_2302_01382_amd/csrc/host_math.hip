@@ -46,3 +46,34 @@ extern "C" int mpq_hutchinson_trace(const double* quad, int64_t P, int64_t rows,
   }
   return MPQ_OK;
 }
+
+// Experiments section, "Compute Latency Estimates": the deployment latency of a mixed-precision
+// model from the kernel latencies of its layers -- layer_us[l][w] measured for layer l at its
+// candidate precision number w, width_index[l] the precision a configuration gives layer l.
+// Layers of an inference pass run one after the other: the estimate is the sum.
+extern "C" int mpq_latency_estimate(const double* layer_us, int n_layers, int n_widths, const int* width_index,
+                                    double* total_us_out) {
+  if (!layer_us || !width_index || !total_us_out) return MPQ_ERR_NULL;
+  if (n_layers <= 0 || n_widths <= 0) return MPQ_ERR_SHAPE;
+  double total = 0.0;
+  for (int l = 0; l < n_layers; ++l) {
+    if (width_index[l] < 0 || width_index[l] >= n_widths) return MPQ_ERR_SHAPE;
+    total += layer_us[(int64_t)l * n_widths + width_index[l]];
+  }
+  *total_us_out = total;
+  return MPQ_OK;
+}
+
+// Model size of a configuration (Table 1, "Size"): parameters times their bit-widths, in bytes.
+extern "C" int mpq_model_size_bytes(const int64_t* parameters, const int* bits, int n_layers, double* bytes_out) {
+  if (!parameters || !bits || !bytes_out) return MPQ_ERR_NULL;
+  if (n_layers <= 0) return MPQ_ERR_SHAPE;
+  double total = 0.0;
+  for (int l = 0; l < n_layers; ++l) {
+    if (parameters[l] < 0) return MPQ_ERR_SHAPE;
+    if (bits[l] < 1 || bits[l] > 64) return MPQ_ERR_BITS;
+    total += (double)parameters[l] * (double)bits[l] / 8.0;
+  }
+  *bytes_out = total;
+  return MPQ_OK;
+}

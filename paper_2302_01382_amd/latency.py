@@ -62,7 +62,16 @@ def time_qgemm(M: int, K: int, N: int, w_storage_bits: int, reps: int = 40, warm
 
 @dataclass
 class LatencyTable:
-    """microseconds per (M, K, N, storage bits)."""
+    """microseconds per (M, K, N, weight storage bits).
+
+    Precision axes: the paper times a kernel per (shape, precision).  On this hardware and in this
+    library the precision of a layer is a pair (weight bits, activation bits), and it maps to a
+    kernel as follows: weights of up to 4 bits travel as packed int4 (half the weight bytes, expanded
+    to int8 on their way into the matrix core), wider ones as int8; activations are int8 codes at
+    every width from 2 to 8 (a 4-bit activation is an int8 code in +-7).  gfx950 has no integer
+    matrix instruction narrower than int8, so the activation width selects no other kernel and no
+    other amount of traffic: the table is indexed by weight storage only, and lookup() accepts the
+    activation width for completeness and ignores it."""
     us: Dict[Tuple[int, int, int, int], float] = field(default_factory=dict)
 
     def measure(self, shapes: Iterable[Shape], storages: Sequence[int] = (8, 4), **kw) -> "LatencyTable":
@@ -72,14 +81,22 @@ class LatencyTable:
                     self.us[(M, K, N, st)] = time_qgemm(M, K, N, st, **kw)
         return self
 
-    def lookup(self, shape: Shape, bits: int) -> float:
+    def lookup(self, shape: Shape, bits: int, act_bits: int = 8) -> float:
+        if not 2 <= act_bits <= 8:
+            raise ValueError("activations are int8 codes of 2..8 bits")
         return self.us[(shape[0], shape[1], shape[2], storage_bits(bits))]
 
-    def estimate_us(self, layers: Sequence[Shape], bits: Sequence[int]) -> float:
-        """Latency estimate of a configuration: the kernel latencies of its layers, added up."""
-        if len(layers) != len(bits):
+    def estimate_us(self, layers: Sequence[Shape], bits: Sequence[int], act_bits: Sequence[int] = None) -> float:
+        """Latency estimate of a configuration: the kernel latencies of its layers, added up
+        (mpq_latency_estimate on the rows of the table that belong to the layers)."""
+        if len(layers) != len(bits) or (act_bits is not None and len(act_bits) != len(bits)):
             raise ValueError("one bit-width per layer")
-        return sum(self.lookup(s, b) for s, b in zip(layers, bits))
+        act_bits = act_bits or [8] * len(bits)
+        for s, b, a in zip(layers, bits, act_bits):
+            self.lookup(s, b, a)   # raises KeyError for a shape that was not measured
+        storages = (8, 4)
+        rows = [[self.us.get((s[0], s[1], s[2], st), float("nan")) for st in storages] for s in layers]
+        return mpq.latency_estimate(rows, [storages.index(storage_bits(b)) for b in bits])
 
     def relative(self, layers: Sequence[Shape], bits: Sequence[int], baseline_bits: int = 8) -> float:
         """Estimated latency relative to every layer at baseline_bits (the paper's relative latency)."""
@@ -87,8 +104,8 @@ class LatencyTable:
 
 
 def footprint_bytes(layers: Sequence[Shape], bits: Sequence[int]) -> float:
-    """Model footprint of a configuration: parameters times their bit-width."""
-    return sum(s[1] * s[2] * b / 8.0 for s, b in zip(layers, bits))
+    """Model footprint of a configuration: parameters times their bit-width (mpq_model_size_bytes)."""
+    return mpq.model_size_bytes([s[1] * s[2] for s in layers], bits)
 
 
 def relative_footprint(layers: Sequence[Shape], bits: Sequence[int], baseline_bits: int = 8) -> float:

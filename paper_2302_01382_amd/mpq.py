@@ -22,7 +22,7 @@ EXPORTS = [
     "mpq_calibrate_absmax",
     "mpq_scale_from_absmax", "mpq_fake_quant", "mpq_quant_error_workspace_bytes",
     "mpq_quant_error", "mpq_quant_error_noalloc", "mpq_noise_inject",
-    "mpq_eqe", "mpq_eqe_channels", "mpq_hutchinson_trace",
+    "mpq_eqe", "mpq_eqe_channels", "mpq_hutchinson_trace", "mpq_latency_estimate", "mpq_model_size_bytes",
     "mpq_sweep_plan_bytes", "mpq_sweep_plan_build", "mpq_calibrate_absmax_batch",
     "mpq_quant_error_batch_workspace_bytes", "mpq_quant_error_batch", "mpq_qgemm_workspace_bytes", "mpq_qgemm",
     "mpq_sse_pair_workspace_bytes", "mpq_sse_pair", "mpq_qgemm_score_workspace_bytes", "mpq_qgemm_score",
@@ -81,6 +81,8 @@ def lib():
         L.mpq_eqe.argtypes = [C.c_double, i64, C.c_double]
         L.mpq_eqe_channels.argtypes = [vp, vp, i64, ci, i64, vp]
         L.mpq_hutchinson_trace.argtypes = [vp, i64, i64, vp, vp]
+        L.mpq_latency_estimate.argtypes = [vp, ci, ci, vp, vp]
+        L.mpq_model_size_bytes.argtypes = [vp, vp, ci, vp]
         L.mpq_sweep_plan_bytes.restype = sz
         L.mpq_sweep_plan_bytes.argtypes = [vp, ci]
         L.mpq_sweep_plan_build.argtypes = [vp, ci, vp, sz]
@@ -293,6 +295,31 @@ def eqe_channels(sse_ch, n: int, absmax_ch):
     out = (C.c_double * s.shape[1])()
     _check(lib().mpq_eqe_channels(s.ctypes.data, m.ctypes.data, m.size, s.shape[1], int(n), out), "mpq_eqe_channels")
     return list(out)
+
+
+def latency_estimate(layer_us, width_index) -> float:
+    """Model latency of a configuration: layer_us [n_layers, n_widths] measured kernel latencies,
+    width_index[l] the candidate precision number of layer l (host arithmetic in the library)."""
+    import numpy as np
+    t = np.ascontiguousarray(layer_us, dtype=np.float64)
+    if t.ndim != 2 or t.shape[0] != len(width_index):
+        raise ValueError("one row of kernel latencies and one width index per layer")
+    idx = (C.c_int * t.shape[0])(*[int(v) for v in width_index])
+    out = C.c_double(0.0)
+    _check(lib().mpq_latency_estimate(t.ctypes.data, t.shape[0], t.shape[1], idx, C.byref(out)), "mpq_latency_estimate")
+    return out.value
+
+
+def model_size_bytes(parameters, bits) -> float:
+    """Parameters times their bit-widths, in bytes (host arithmetic in the library)."""
+    n = len(parameters)
+    if n != len(bits):
+        raise ValueError("one bit-width per layer")
+    p = (C.c_int64 * n)(*[int(v) for v in parameters])
+    b = (C.c_int * n)(*[int(v) for v in bits])
+    out = C.c_double(0.0)
+    _check(lib().mpq_model_size_bytes(p, b, n, C.byref(out)), "mpq_model_size_bytes")
+    return out.value
 
 
 def hutchinson_trace(quad, rows: int):
