@@ -529,7 +529,11 @@ def _timed_calls(torch, calls, reps):
 # HBM traffic per launch of the batched sweep kernels over configuration 4, bytes, from the rocprofv3
 # counter runs summarised in profiles/cfg4_batched_sweep_hbm_traffic.txt (FETCH_SIZE and WRITE_SIZE
 # scaled by what the same counters read for a plain device copy of known size in the same run).
-TRAFFIC_BYTES_PER_LAUNCH_CFG4 = {}
+TRAFFIC_BYTES_PER_LAUNCH_CFG4 = {   # (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000) KiB of the call's two kernels
+    "calibrate_absmax_batch": ((590499.1 + 451.5) * 2.0 + 1319.4 + 3.0) * 1024.0,
+    "quant_error_batch_per_tensor": ((590230.9 + 157.5) * 2.0 + 360.0 + 7.5) * 1024.0,
+    "quant_error_batch_per_row": (591782.5 * 2.0 + 12533.1) * 1024.0,
+}
 
 
 def bench_sweep_cfg4(torch, mpq, workloads, steps, warmup):
@@ -551,12 +555,25 @@ def bench_sweep_cfg4(torch, mpq, workloads, steps, warmup):
         step()
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / steps
-    us = _timed_calls(torch, {
-        "calibrate_absmax_batch": lambda: mpq.calibrate_absmax_batch(plan),
-        "quant_error_batch_per_tensor": lambda: mpq.quant_error_batch(plan, mpq.PER_TENSOR),
-        "quant_error_batch_per_row": lambda: mpq.quant_error_batch(plan, mpq.PER_ROW),
-        "quant_error_batch_both_in_one_read": lambda: mpq.quant_error_batch(plan, mpq.SWEEP_TENSOR_AND_ROW),
-    }, steps)
+    # kernel-level figures: the same steps again with HIP events (on the launch stream) around every
+    # call, the host kept ahead of the GPU by a spin kernel; a call is its main kernel plus a
+    # finishing kernel of a few microseconds
+    names = ("calibrate_absmax_batch", "quant_error_batch_per_tensor", "quant_error_batch_per_row")
+    calls = (lambda: mpq.calibrate_absmax_batch(plan), lambda: mpq.quant_error_batch(plan, mpq.PER_TENSOR),
+             lambda: mpq.quant_error_batch(plan, mpq.PER_ROW))
+    pairs = {k: [] for k in names}
+    torch.cuda._sleep(3_000_000)
+    for _ in range(steps):
+        for k, fn in zip(names, calls):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            pairs[k].append((e0, e1))
+    torch.cuda.synchronize()
+    us = {k: sum(a.elapsed_time(b) for a, b in v) * 1e3 / len(v) for k, v in pairs.items()}
+    us.update(_timed_calls(torch, {
+        "quant_error_batch_both_in_one_read": lambda: mpq.quant_error_batch(plan, mpq.SWEEP_TENSOR_AND_ROW)}, steps))
     gbs = {k: 4.0 * n / v / 1e3 for k, v in us.items()}
     # the noise levels: one call per tensor, seven planes each (4 bytes read + 28 written per element)
     noisy = {}
@@ -599,11 +616,14 @@ def bench_sweep_cfg4(torch, mpq, workloads, steps, warmup):
     }, host
 
 
-def gemm_shape_rows(workloads, reps=30, warmup=4):
+def gemm_shape_rows(workloads, reps=30, warmup=4, only=None):
+    """only: "MxKxN" restricts the table to that one shape (what the counter passes profile)."""
     from paper_2302_01382_amd import latency as lat
     rows = []
     for cfg, shapes in (("cfg2", workloads.CFG2), ("cfg3", workloads.CFG3), ("cfg5", workloads.CFG5)):
         for g in shapes:
+            if only and only != "%dx%dx%d" % (g.M, g.K, g.N):
+                continue
             for st in (8, 4):
                 us = lat.time_qgemm(g.M, g.K, g.N, st, reps=reps, warmup=warmup)
                 ops = 2.0 * g.M * g.N * g.K
@@ -969,7 +989,7 @@ def run_gemm_shapes(torch, mpq, workloads, args):
     weights, per-output-channel scales, fp32 output), operands rotated through more than the
     memory-side cache holds: time per launch, TOP/s, fraction of the int8 matrix peak, and
     fraction of the shape's own roofline min(matrix peak, arithmetic intensity x HBM peak)."""
-    rows = gemm_shape_rows(workloads)
+    rows = gemm_shape_rows(workloads, only=args.shape)
     best = max(rows, key=lambda r: r["tops"])
     peaks = measured_peaks(torch, mpq)
     for r in rows:
@@ -1024,6 +1044,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", choices=["cfg2", "cfg3", "cfg4", "cfg4-1stream", "cfg4-unfused", "cfg5", "cfg5-twopass", "cfg5-unfused", "search", "latency", "hutchinson", "gemm", "headline", "sweep"], default="headline")
+    ap.add_argument("--shape", default=None, help="gemm: only this configured shape, as MxKxN (e.g. 16384x4096x1024)")
     ap.add_argument("--cpu-sample-rows", type=int, default=2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--streams", type=int, default=4,
