@@ -17,8 +17,18 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
-OBJ = os.path.join(HERE, "_build")
-LIB = os.path.join(HERE, "libmpq.so")
+# MPQ_SANITIZE_HOST=1: a second copy of the library whose HOST code (argument checks, plan
+# builders, searches, host arithmetic) is instrumented with the address and undefined-behaviour
+# sanitizers; device code is unchanged.  For the CPU test suite on a GPU-less machine:
+#   LD_PRELOAD="$(gcc -print-file-name=libasan.so) $(gcc -print-file-name=libubsan.so)" \
+#       ASAN_OPTIONS=detect_leaks=0 MPQ_SANITIZE_HOST=1 python -m pytest tests -m "not gpu"
+SANITIZE_HOST = os.environ.get("MPQ_SANITIZE_HOST", "0") not in ("", "0")
+OBJ = os.path.join(HERE, "_build_san" if SANITIZE_HOST else "_build")
+LIB = os.path.join(HERE, "libmpq_san.so" if SANITIZE_HOST else "libmpq.so")
+# (the function-type and vptr checks are left out: the runtime that is preloaded is gcc's, which
+# has no handler for them)
+SAN_FLAGS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host",
+             "-fno-sanitize=function,vptr", "-Xarch_host", "-fno-omit-frame-pointer"]
 
 # -ffp-contract=off: every fused multiply-add in the kernels is written explicitly.
 # packed fp32 instructions are switched off for the device compiler (the host pass warns that it
@@ -75,14 +85,15 @@ def build_lib(verbose: bool = False, incremental: bool = False, jobs: int = 8) -
         fresh = (incremental and os.path.exists(obj)
                  and os.path.getmtime(obj) > max(os.path.getmtime(src), newest_header))
         if not fresh:
-            todo.append([hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-                         "-c", src, "-o", obj])
+            todo.append([hipcc, *HIPCC_FLAGS, *(SAN_FLAGS if SANITIZE_HOST else []), "-I", os.path.join(ROOT, "include"),
+                         "-I", CSRC, "-c", src, "-o", obj])
     # stale objects of sources that no longer exist must not be linked
     for stray in set(glob.glob(os.path.join(OBJ, "*.o"))) - set(objs):
         os.remove(stray)
     with ThreadPoolExecutor(max(1, jobs)) as ex:
         list(ex.map(lambda c: _run(c, verbose), todo))
-    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB + ".tmp", *objs], verbose)
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *(SAN_FLAGS if SANITIZE_HOST else []), "-o", LIB + ".tmp",
+          *objs], verbose)
     os.replace(LIB + ".tmp", LIB)
     return LIB
 
