@@ -85,3 +85,50 @@ def test_batched_sweep_of_a_set_lying_on_the_grid_is_zero():
     for i, b in enumerate((2, 4, 8)):
         assert float(plan.sse_tensor[i][0, b - 2]) == 0.0
         assert float(plan.sse_row[i][:, b - 2].abs().max()) == 0.0
+
+
+def test_batched_sweep_and_noalloc_call_replay_in_a_hip_graph():
+    """The calls only enqueue kernels (no memset nodes, no allocation), so a captured sweep replays:
+    three replays with eager work and synchronisations between them, every replay checked against
+    the eager result on fresh data written into the same tensors."""
+    import torch
+    xs = _tensors(54)
+    dx = [_dev(x) for x in xs]
+    plan = mpq.sweep_plan_build(dx)
+    big = dx[6]                                              # 1000 x 516
+    am_big = torch.empty(1, dtype=torch.float32, device="cuda")
+    out_na = torch.empty((1, 7), dtype=torch.float64, device="cuda")
+    ws = mpq.Workspace()
+    ws.get(1 << 20)
+
+    def sweep():
+        mpq.calibrate_absmax_batch(plan)
+        mpq.quant_error_batch(plan, mpq.PER_TENSOR)
+        mpq.quant_error_batch(plan, mpq.PER_ROW)
+        mpq.calibrate_absmax(big, out=am_big, ws=ws)
+        mpq.quant_error_noalloc(big, am_big, out_na)
+
+    sweep()                                                  # sizes every workspace before the capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        sweep()
+    r = np.random.Generator(np.random.PCG64(55))
+    for it in range(3):
+        for t in dx:                                         # new values in place: the graph holds addresses only
+            t.copy_(torch.from_numpy((r.standard_normal(tuple(t.shape)) * (it + 1)).astype(np.float32)))
+        plan.sse_tensor_all.fill_(-1.0)
+        plan.sse_row_all.fill_(-1.0)
+        out_na.fill_(-1.0)
+        g.replay()
+        torch.cuda.synchronize()
+        got = (plan.sse_tensor_all.clone(), plan.sse_row_all.clone(), plan.absmax_row_all.clone(), out_na.clone())
+        sweep()                                              # the same, eagerly
+        torch.cuda.synchronize()
+        want = (plan.sse_tensor_all, plan.sse_row_all, plan.absmax_row_all, out_na)
+        for a, b in zip(got, want):
+            assert torch.equal(a, b)
+        assert float(out_na.min()) >= 0.0
+        # and against the oracle, once per replay, on one tensor
+        x6 = big.cpu().numpy()
+        np.testing.assert_allclose(got[3].cpu().numpy(), oracle.quant_error(x6, oracle.absmax(x6)), rtol=RTOL_SSE)
