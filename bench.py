@@ -652,7 +652,9 @@ def bench_gemm_block(torch, mpq, workloads, peaks):
                     "per-output-channel scales, fp32 output",
         "tops_all_shapes": ops / us / 1e6, "tops_k_ge_2048_shapes": ops_k / us_k / 1e6,
         "frac_of_int8_mfma_peak_k_ge_2048_shapes": ops_k / us_k / 1e6 / INT8_PEAK_TOPS,
-        "w4_not_slower_than_w8_within_2_percent": all(b["us"] <= 1.02 * a["us"] for a, b in zip(rows[0::2], rows[1::2])),
+        "w4_over_w8_time_ratio": {"worst": max(round(b["us"] / a["us"], 3) for a, b in zip(rows[0::2], rows[1::2])),
+                                  "best": min(round(b["us"] / a["us"], 3) for a, b in zip(rows[0::2], rows[1::2])),
+                                  "all_shapes_together": round(sum(r["us"] for r in rows[1::2]) / sum(r["us"] for r in rows[0::2]), 3)},
         "shapes": rows,
         "roofline": {"bound": "mfma", "achieved": best["tops"], "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
                      "frac": best["tops"] / INT8_PEAK_TOPS, "traffic": None, "bar": 0.60,
