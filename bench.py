@@ -198,16 +198,16 @@ def roofline_of(m, traffic_kib=None):
         roof = {"bound": "hbm", "achieved": rec.bytes[dom] / steps / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "algorithmic_per_launch": rec.bytes[dom] / steps / n_launch}
     if dom == "quant_error":
-        # The sweep is bound by the vector ALUs, not by HBM: 29 lane-operations per element (7
-        # bit-widths x 4 + one clip) at 4 bytes per element is 7.25 lane-op per byte, above the
+        # The sweep is bound by the vector ALUs, not by HBM: 28 lane-operations per element (6
+        # bit-widths x 4, 3 for two bits, one clip) at 4 bytes per element is 7 lane-op per byte, above the
         # chip's ratio of 39.3 T lane-op/s (256 CUs x 64 lanes x 2.4 GHz, packed fp32 math is not
         # used) to 8 TB/s = 4.9.  Its roofline is therefore the ALU one; the HBM view is kept next to it.
         hbm = dict(roof)
         hbm["frac"] = hbm["achieved"] / hbm["peak"]
-        lane_ops = rec.bytes[dom] / steps / 4 * 29
+        lane_ops = rec.bytes[dom] / steps / 4 * 28
         roof = {"bound": "alu", "achieved": lane_ops / (ms * 1e-3) / 1e12, "peak": ALU_PEAK_TLANEOPS,
                 "unit": "T lane-op/s", "algorithmic_per_launch": lane_ops / n_launch,
-                "lane_ops_per_element": 29,
+                "lane_ops_per_element": 28,
                 "hbm_view": {k: hbm[k] for k in ("achieved", "peak", "unit", "frac", "algorithmic_per_launch")}}
     roof["frac"] = roof["achieved"] / roof["peak"]
     t = None if traffic_kib is None else traffic_kib.get(dom)
@@ -610,9 +610,9 @@ def bench_sweep_cfg4(torch, mpq, workloads, steps, warmup):
                      "frac": gbs[slow] / HBM_PEAK_GBS, "traffic": TRAFFIC_BYTES_PER_LAUNCH_CFG4.get(slow),
                      "kernel": slow + " (b = 2..8, all 96 tensors in one launch + a finishing launch)",
                      "algorithmic_per_launch": 4.0 * n, "avg_launch_us": us[slow], "bar": 0.70,
-                     "alu_view": {"lane_ops_per_element": 29, "achieved": 29.0 * n / us[slow] / 1e6,
+                     "alu_view": {"lane_ops_per_element": 28, "achieved": 28.0 * n / us[slow] / 1e6,
                                   "peak": ALU_PEAK_TLANEOPS, "unit": "T lane-op/s",
-                                  "frac": 29.0 * n / us[slow] / 1e6 / ALU_PEAK_TLANEOPS}},
+                                  "frac": 28.0 * n / us[slow] / 1e6 / ALU_PEAK_TLANEOPS}},
     }, host
 
 
