@@ -54,7 +54,7 @@ if ROOT not in sys.path:
 METRIC = "qgemm int8 TOPS (% MFMA peak); quant+error sweep GB/s (% HBM peak)"
 HBM_PEAK_GBS = 8000.0
 INT8_PEAK_TOPS = 5000.0
-ALU_PEAK_TLANEOPS = 256 * 64 * 2.4e9 / 1e12   # 256 CUs x 64 lanes x 2.4 GHz, no packed math
+ALU_PEAK_TLANEOPS = 256 * 4 * 32 * 2.4e9 / 1e12   # 256 CUs x 4 SIMDs x 32 lanes per clock x 2.4 GHz = 78.6 (157.3 TFLOP/s fp32)
 LAMBDA = 0.28867513  # 1/sqrt(12): noise with the variance of uniform rounding error of one step
 
 # HBM traffic per main-stream launch of configuration 2 (activation tensor of a layer, averaged
@@ -198,17 +198,13 @@ def roofline_of(m, traffic_kib=None):
         roof = {"bound": "hbm", "achieved": rec.bytes[dom] / steps / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "algorithmic_per_launch": rec.bytes[dom] / steps / n_launch}
     if dom == "quant_error":
-        # The sweep is bound by the vector ALUs, not by HBM: 28 lane-operations per element (6
-        # bit-widths x 4, 3 for two bits, one clip) at 4 bytes per element is 7 lane-op per byte, above the
-        # chip's ratio of 39.3 T lane-op/s (256 CUs x 64 lanes x 2.4 GHz, packed fp32 math is not
-        # used) to 8 TB/s = 4.9.  Its roofline is therefore the ALU one; the HBM view is kept next to it.
-        hbm = dict(roof)
-        hbm["frac"] = hbm["achieved"] / hbm["peak"]
+        # 28 lane-operations per element (6 bit-widths x 4, 3 for two bits, one clip) at 4 bytes per
+        # element is 7 lane-op per byte, below the chip's ratio of 78.6 T lane-op/s to 8 TB/s = 9.8:
+        # the sweep is bound by HBM; the vector-ALU view is kept next to it
         lane_ops = rec.bytes[dom] / steps / 4 * 28
-        roof = {"bound": "alu", "achieved": lane_ops / (ms * 1e-3) / 1e12, "peak": ALU_PEAK_TLANEOPS,
-                "unit": "T lane-op/s", "algorithmic_per_launch": lane_ops / n_launch,
-                "lane_ops_per_element": 28,
-                "hbm_view": {k: hbm[k] for k in ("achieved", "peak", "unit", "frac", "algorithmic_per_launch")}}
+        roof["alu_view"] = {"lane_ops_per_element": 28, "achieved": lane_ops / (ms * 1e-3) / 1e12,
+                            "peak": ALU_PEAK_TLANEOPS, "unit": "T lane-op/s",
+                            "frac": lane_ops / (ms * 1e-3) / 1e12 / ALU_PEAK_TLANEOPS}
     roof["frac"] = roof["achieved"] / roof["peak"]
     t = None if traffic_kib is None else traffic_kib.get(dom)
     roof["traffic"] = None if t is None else t * 1024.0
@@ -601,9 +597,9 @@ def bench_sweep_cfg4(torch, mpq, workloads, steps, warmup):
         "call_gbs_at_4_bytes_per_element": {k: round(v, 1) for k, v in gbs.items()},
         "call_frac_of_hbm_peak": {k: round(v / HBM_PEAK_GBS, 4) for k, v in gbs.items()},
         "both_in_one_read_alu_view": {
-            "lane_ops_per_element": 57,
-            "t_lane_ops_per_s": round(57.0 * n / us["quant_error_batch_both_in_one_read"] / 1e6, 2),
-            "frac_of_alu_peak": round(57.0 * n / us["quant_error_batch_both_in_one_read"] / 1e6 / ALU_PEAK_TLANEOPS, 4)},
+            "lane_ops_per_element": 56,
+            "t_lane_ops_per_s": round(56.0 * n / us["quant_error_batch_both_in_one_read"] / 1e6, 2),
+            "frac_of_alu_peak": round(56.0 * n / us["quant_error_batch_both_in_one_read"] / 1e6 / ALU_PEAK_TLANEOPS, 4)},
         "noise_7_levels": {"ms_per_sweep": noise_ms, "bytes_per_sweep": 32 * n, "gbs": 32.0 * n / noise_ms / 1e6,
                            "frac_of_hbm_peak": 32.0 * n / noise_ms / 1e6 / HBM_PEAK_GBS, "launches": len(tensors)},
         "roofline": {"bound": "hbm", "achieved": gbs[slow], "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -963,15 +959,18 @@ def run_hutchinson(torch, mpq, workloads, args):
 
 
 def measured_peaks(torch, mpq):
-    """What this chip sustains, measured in place: a plain device copy (HBM) and the int8 matrix
+    """What this chip sustains, measured in place: a plain device copy (HBM), the int8 matrix
     cores issuing from registers, on constant-byte and on uniformly random operands (the clock under
-    matrix load depends on how much the operand bits toggle)."""
+    matrix load depends on how much the operand bits toggle), and the vector ALUs on the error
+    sweep's arithmetic."""
     n = mpq.diag_mfma_operand_bytes()
     g = torch.Generator(device="cuda").manual_seed(3)
     rnd = torch.randint(-127, 128, (n,), dtype=torch.int8, device="cuda", generator=g)
     const = torch.full((n,), 3, dtype=torch.int8, device="cuda")
     out = {"int8_mfma_tops_constant_bytes": round(mpq.diag_mfma_rate(const), 1),
-           "int8_mfma_tops_random_bytes": round(mpq.diag_mfma_rate(rnd), 1)}
+           "int8_mfma_tops_random_bytes": round(mpq.diag_mfma_rate(rnd), 1),
+           # the error sweep's own arithmetic on registers: the vector-ALU ceiling of the sweep kernels
+           "sweep_arithmetic_t_lane_ops_per_s": round(mpq.diag_sweep_alu_rate(), 1)}
     src = torch.empty(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB, more than the memory-side cache
     dst = torch.empty_like(src)
     dst.copy_(src)
@@ -1043,8 +1042,11 @@ def run_latency(torch, mpq, workloads, args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=None,
+                    help="timed steps (default: 100 for the sweep workloads, whose step is 0.7 ms; 20 otherwise)")
+    ap.add_argument("--warmup", type=int, default=None,
+                    help="untimed steps before them (default: 60 for the sweep workloads: from idle the chip needs "
+                         "some 15 ms of work before its clocks are up, and the first 20 steps run 15 %% slower; 3 otherwise)")
     ap.add_argument("--workload", choices=["cfg2", "cfg3", "cfg4", "cfg4-1stream", "cfg4-unfused", "cfg5", "cfg5-twopass", "cfg5-unfused", "search", "latency", "hutchinson", "gemm", "headline", "sweep"], default="headline")
     ap.add_argument("--shape", default=None, help="gemm: only this configured shape, as MxKxN (e.g. 16384x4096x1024)")
     ap.add_argument("--cpu-sample-rows", type=int, default=2048)
@@ -1059,6 +1061,11 @@ def main():
         print("bench.py: this build measures ONE GPU only (the path has no collectives); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
+    sweep_like = args.workload in ("headline", "sweep")
+    if args.steps is None:
+        args.steps = 100 if sweep_like else 20
+    if args.warmup is None:
+        args.warmup = 60 if sweep_like else 3
 
     import torch
     from paper_2302_01382_amd import mpq, workloads

@@ -416,6 +416,14 @@ size_t mpq_diag_mfma_operand_bytes(void);
 int mpq_diag_mfma_rate(const void* operands, size_t operand_bytes, int iters, int* sink, double* ops_out,
                        void* stream);
 
+/* Launches a kernel that does nothing but the arithmetic of the error sweep of Sec. 3.2.1 Eq. 2 for
+ * b = 2..8 (the code mpq_quant_error runs per element) on elements held in registers: eight
+ * workgroups of 256 threads per CU, 16 elements per lane and iteration, no memory traffic in the
+ * loop.  Timing it gives the vector-ALU ceiling of the sweep kernels on this chip.  lane_ops_out
+ * (host, nullable) receives the number of lane-operations of the launch (28 per element).
+ * sink: device float[1], scratch. */
+int mpq_diag_sweep_alu_rate(int iters, float* sink, double* lane_ops_out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -4,10 +4,12 @@
 //
 // Per element and bit-width: t = fma(xc, inv_b, 1.5*2^23); q = t - 1.5*2^23; e = fma(q, scale_b, -x);
 // acc_b = fma(e, e, acc_b) -- four VALU operations, with xc = clip(x, +-m) computed once (it
-// replaces the clamp of the code, see fake_quant.hip; two bits take three, see sweep.hpp).  28 lane-operations per element for the
-// full sweep b = 2..8 against 4 bytes of HBM traffic: the kernel sits where the vector-ALU and
-// HBM rooflines meet, so nothing else is allowed into the inner loop (constants live in
-// registers for the whole kernel, loads are 128-bit and four deep).
+// replaces the clamp of the code, see fake_quant.hip; two bits take three, see sweep.hpp).
+// 28 lane-operations per element for the full sweep b = 2..8 against 4 bytes of HBM traffic: a
+// quarter below what the vector ALUs take
+// from registers (mpq_diag_sweep_alu_rate), so the kernel is bound by HBM as long as nothing else
+// gets into the inner loop (constants live in registers for the whole kernel, loads are 128-bit
+// and four deep).
 //
 // Reproducibility: per-lane fp32 partial sums (a lane sees at most ~4k elements), fixed-order
 // DPP wave reduction, then double precision across waves / blocks in a fixed order.  No float

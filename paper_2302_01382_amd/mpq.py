@@ -28,7 +28,7 @@ EXPORTS = [
     "mpq_sse_pair_workspace_bytes", "mpq_sse_pair", "mpq_qgemm_score_workspace_bytes", "mpq_qgemm_score",
     "mpq_search_bisection", "mpq_search_greedy", "mpq_noise_inject_sweep",
     "mpq_fake_quant_scales", "mpq_scale_grad_workspace_bytes", "mpq_scale_grad", "mpq_scale_sgd_step", "mpq_qgemm_act", "mpq_qgemm_act_codes",
-    "mpq_diag_mfma_operand_bytes", "mpq_diag_mfma_rate", "mpq_fake_quant_step", "mpq_stack_evaluate_workspace_bytes", "mpq_stack_evaluate", "mpq_rademacher", "mpq_hutchinson_quad_workspace_bytes", "mpq_hutchinson_quad", "mpq_hutchinson_quad_signs",
+    "mpq_diag_mfma_operand_bytes", "mpq_diag_mfma_rate", "mpq_diag_sweep_alu_rate", "mpq_fake_quant_step", "mpq_stack_evaluate_workspace_bytes", "mpq_stack_evaluate", "mpq_rademacher", "mpq_hutchinson_quad_workspace_bytes", "mpq_hutchinson_quad", "mpq_hutchinson_quad_signs",
 ]
 
 ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
@@ -102,6 +102,7 @@ def lib():
         L.mpq_diag_mfma_operand_bytes.argtypes = []
         L.mpq_diag_mfma_operand_bytes.restype = C.c_size_t
         L.mpq_diag_mfma_rate.argtypes = [vp, C.c_size_t, ci, vp, C.POINTER(C.c_double), vp]
+        L.mpq_diag_sweep_alu_rate.argtypes = [ci, vp, C.POINTER(C.c_double), vp]
         L.mpq_fake_quant_step.argtypes = [vp, i64, i64, vp, ci, vp, vp, vp, vp, vp]
         L.mpq_stack_evaluate_workspace_bytes.argtypes = [vp, ci, i64]
         L.mpq_stack_evaluate_workspace_bytes.restype = C.c_size_t
@@ -551,6 +552,27 @@ def diag_mfma_rate(operands, iters: int = 2048, reps: int = 5) -> float:
     def launch():
         _check(lib().mpq_diag_mfma_rate(_ptr(operands), nbytes, iters, _ptr(sink), C.byref(ops), _stream()),
                "mpq_diag_mfma_rate")
+
+    launch()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        launch()
+    e1.record()
+    torch.cuda.synchronize()
+    return ops.value * reps / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
+
+def diag_sweep_alu_rate(iters: int = 1000, reps: int = 5) -> float:
+    """Measured rate, in T lane-operations per second, of the error sweep's arithmetic (b = 2..8, 28
+    lane-operations per element) on elements held in registers: a measurement aid."""
+    torch = _torch()
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    ops = C.c_double(0.0)
+
+    def launch():
+        _check(lib().mpq_diag_sweep_alu_rate(iters, _ptr(sink), C.byref(ops), _stream()), "mpq_diag_sweep_alu_rate")
 
     launch()
     torch.cuda.synchronize()

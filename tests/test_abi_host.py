@@ -117,6 +117,10 @@ def test_diag_mfma_rate_validation():
     assert f(FAKE16, need - 1, 16, FAKE, None, None) == mpq.ERR_WORKSPACE
     assert f(C.c_void_p(0x10008), need, 16, FAKE, None, None) == mpq.ERR_ALIGN
     assert f(FAKE16, need, 0, FAKE, None, None) == mpq.ERR_SHAPE
+    g = L.mpq_diag_sweep_alu_rate
+    assert g(16, None, None, None) == mpq.ERR_NULL
+    assert g(0, FAKE, None, None) == mpq.ERR_SHAPE
+    assert g((1 << 20) + 1, FAKE, None, None) == mpq.ERR_SHAPE
 
 
 @needs_no_gpu
