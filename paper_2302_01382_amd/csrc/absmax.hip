@@ -75,7 +75,7 @@ __global__ __launch_bounds__(kBlock) void absmax_rows(const float* __restrict__ 
   if (VEC) {  // cols % 4 == 0 and x 16-byte aligned: every row start is aligned
     const float4* r4 = reinterpret_cast<const float4*>(row);
     for (int64_t i = (c0 >> 2) + lane; i < (c1 >> 2); i += kWave) {
-      const float4 a = r4[i];
+      const float4 a = load_stream(r4 + i);
       m = fmaxf(m, fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))));
     }
   } else {

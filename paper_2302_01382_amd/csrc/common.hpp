@@ -143,6 +143,21 @@ __device__ __forceinline__ float code_f(float x, float inv, float qmax) {
   return __builtin_amdgcn_fmed3f(q, -qmax, qmax);
 }
 
+// Streaming access: a tensor that a kernel reads once is loaded non-temporally (the `nt` bit of
+// the global load), so that it passes through the caches without displacing lines somebody will
+// use again.  Measured on MI355X: the max calibration over 1.2 GB of weights reads 6.5 TB/s with it
+// and 5.7 TB/s without, the error sweep 5.8-6.0 against 5.2-5.4.  The address-space cast also tells
+// the compiler that the pointer is a global one where it cannot see that (pointers read from a
+// table in memory would otherwise become flat loads).
+__device__ __forceinline__ float4 load_stream(const float4* p) {
+  typedef float v4f __attribute__((ext_vector_type(4)));
+  const v4f v = __builtin_nontemporal_load((const __attribute__((address_space(1))) v4f*)p);
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ float load_stream(const float* p) {
+  return __builtin_nontemporal_load((const __attribute__((address_space(1))) float*)p);
+}
+
 // Visits every float4 of x4[0, n4) that the tile round-robin deals to this block: f(value, index).
 template <typename F>
 __device__ __forceinline__ void for_each_vec4_tiled(const float4* __restrict__ x4, int64_t n4, F&& f) {
@@ -153,14 +168,14 @@ __device__ __forceinline__ void for_each_vec4_tiled(const float4* __restrict__ x
     if ((t + 1) * tile <= n4) {  // block-uniform
       float4 v[kTileVec];
 #pragma unroll
-      for (int u = 0; u < kTileVec; ++u) v[u] = x4[base + u * kBlock];
+      for (int u = 0; u < kTileVec; ++u) v[u] = load_stream(x4 + base + u * kBlock);
 #pragma unroll
       for (int u = 0; u < kTileVec; ++u) f(v[u], base + u * kBlock);
     } else {
 #pragma unroll
       for (int u = 0; u < kTileVec; ++u) {
         const int64_t i = base + u * kBlock;
-        if (i < n4) f(x4[i], i);
+        if (i < n4) f(load_stream(x4 + i), i);
       }
     }
   }
@@ -176,14 +191,15 @@ __device__ __forceinline__ void for_each_vec4_pair_tiled(const float4* __restric
   for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
     const int64_t base = t * tile + threadIdx.x;
     if ((t + 1) * tile <= n4) {
-      const float4 a0 = a4[base], b0 = b4[base], a1 = a4[base + kBlock], b1 = b4[base + kBlock];
+      const float4 a0 = load_stream(a4 + base), b0 = load_stream(b4 + base), a1 = load_stream(a4 + base + kBlock),
+                   b1 = load_stream(b4 + base + kBlock);
       f(a0, b0);
       f(a1, b1);
     } else {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const int64_t i = base + u * kBlock;
-        if (i < n4) f(a4[i], b4[i]);
+        if (i < n4) f(load_stream(a4 + i), load_stream(b4 + i));
       }
     }
   }

@@ -115,10 +115,11 @@ __global__ __launch_bounds__(kBlock) void qe_rows(const float* __restrict__ x, i
     int64_t i = (c0 >> 2) + lane;
     const int64_t e4 = c1 >> 2;
     for (; i + 3 * kWave < e4; i += 4 * kWave) {
-      const float4 a = r4[i], b = r4[i + kWave], c = r4[i + 2 * kWave], d = r4[i + 3 * kWave];
+      const float4 a = load_stream(r4 + i), b = load_stream(r4 + i + kWave), c = load_stream(r4 + i + 2 * kWave),
+                   d = load_stream(r4 + i + 3 * kWave);
       s.add4(a); s.add4(b); s.add4(c); s.add4(d);
     }
-    for (; i < e4; i += kWave) s.add4(r4[i]);
+    for (; i < e4; i += kWave) s.add4(load_stream(r4 + i));
   } else {
     for (int64_t c = c0 + lane; c < c1; c += kWave) s.add(row[c]);
   }
@@ -164,10 +165,11 @@ __global__ __launch_bounds__(kBlock) void qe_rows_sub(const float* __restrict__ 
   const int64_t e4 = cols >> 2;
   int64_t i = lr;
   for (; i + 3 * LPR < e4; i += 4 * LPR) {
-    const float4 a = r4[i], b = r4[i + LPR], c = r4[i + 2 * LPR], d = r4[i + 3 * LPR];
+    const float4 a = load_stream(r4 + i), b = load_stream(r4 + i + LPR), c = load_stream(r4 + i + 2 * LPR),
+                 d = load_stream(r4 + i + 3 * LPR);
     s.add4(a); s.add4(b); s.add4(c); s.add4(d);
   }
-  for (; i < e4; i += LPR) s.add4(r4[i]);
+  for (; i < e4; i += LPR) s.add4(load_stream(r4 + i));
 #pragma unroll
   for (int b = 0; b < NB; ++b) {
     const float w = LPR == 16 ? row16_sum(s.acc[b]) : wave_sum(s.acc[b]);

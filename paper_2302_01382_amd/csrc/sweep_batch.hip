@@ -88,14 +88,15 @@ __device__ __forceinline__ void absmax_rows_of_item(const PlanTensor& T, int ind
     float m = 0.0f;
     int64_t i = lr;
     for (; i + 3 * LPR < e4; i += 4 * LPR) {
-      const float4 a = r4[i], b = r4[i + LPR], c = r4[i + 2 * LPR], d = r4[i + 3 * LPR];
+      const float4 a = load_stream(r4 + i), b = load_stream(r4 + i + LPR), c = load_stream(r4 + i + 2 * LPR),
+                   d = load_stream(r4 + i + 3 * LPR);
       m = fmaxf(m, fmaxf(fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))),
                          fmaxf(fmaxf(fabsf(b.x), fabsf(b.y)), fmaxf(fabsf(b.z), fabsf(b.w)))));
       m = fmaxf(m, fmaxf(fmaxf(fmaxf(fabsf(c.x), fabsf(c.y)), fmaxf(fabsf(c.z), fabsf(c.w))),
                          fmaxf(fmaxf(fabsf(d.x), fabsf(d.y)), fmaxf(fabsf(d.z), fabsf(d.w)))));
     }
     for (; i < e4; i += LPR) {
-      const float4 a = r4[i];
+      const float4 a = load_stream(r4 + i);
       m = fmaxf(m, fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))));
     }
     if (LPR == 16) {
@@ -149,13 +150,13 @@ __global__ __launch_bounds__(kBlock) void qe_flat_batch(const void* __restrict__
     if (base - threadIdx.x + tile <= n4) {  // workgroup-uniform
       float4 v[kTileVec];
 #pragma unroll
-      for (int u = 0; u < kTileVec; ++u) v[u] = x4[base + u * kBlock];
+      for (int u = 0; u < kTileVec; ++u) v[u] = load_stream(x4 + base + u * kBlock);
 #pragma unroll
       for (int u = 0; u < kTileVec; ++u) s.add4(v[u]);
     } else {
 #pragma unroll
       for (int u = 0; u < kTileVec; ++u)
-        if (base + u * kBlock < n4) s.add4(x4[base + u * kBlock]);
+        if (base + u * kBlock < n4) s.add4(load_stream(x4 + base + u * kBlock));
     }
   }
   __shared__ float sm[kBlock / kWave][NB];
@@ -233,12 +234,13 @@ __device__ __forceinline__ void qe_rows_of_item(const PlanTensor& T, int index, 
     const float4* r4 = reinterpret_cast<const float4*>(T.t.x + r * T.t.cols);
     int64_t i = lr;
     for (; i + 3 * LPR < e4; i += 4 * LPR) {
-      const float4 a = r4[i], b = r4[i + LPR], c = r4[i + 2 * LPR], d = r4[i + 3 * LPR];
+      const float4 a = load_stream(r4 + i), b = load_stream(r4 + i + LPR), c = load_stream(r4 + i + 2 * LPR),
+                   d = load_stream(r4 + i + 3 * LPR);
       s.add4(a); s.add4(b); s.add4(c); s.add4(d);
       if (BOTH && live) { st.add4(a); st.add4(b); st.add4(c); st.add4(d); }
     }
     for (; i < e4; i += LPR) {
-      const float4 a = r4[i];
+      const float4 a = load_stream(r4 + i);
       s.add4(a);
       if (BOTH && live) st.add4(a);
     }
