@@ -210,7 +210,7 @@ template <int NB, int LPR, bool BOTH>
 __device__ __forceinline__ void qe_rows_of_item(const PlanTensor& T, int index, int b_lo, Sweep<NB>& st) {
   constexpr int RG = kBlock / LPR;
   const int lr = threadIdx.x % LPR;
-  const int64_t e4 = T.t.cols >> 2;
+  const int e4 = (int)(T.t.cols >> 2);  // at most 4096
   for (int g = 0; g < kRowGroupsPerItem; ++g) {
     int64_t r = ((int64_t)index * kRowGroupsPerItem + g) * RG + threadIdx.x / LPR;
     const bool live = r < T.t.rows;
@@ -232,7 +232,7 @@ __device__ __forceinline__ void qe_rows_of_item(const PlanTensor& T, int index, 
       s.acc[b] = 0.0f;
     }
     const float4* r4 = reinterpret_cast<const float4*>(T.t.x + r * T.t.cols);
-    int64_t i = lr;
+    int i = lr;
     for (; i + 3 * LPR < e4; i += 4 * LPR) {
       const float4 a = load_stream(r4 + i), b = load_stream(r4 + i + LPR), c = load_stream(r4 + i + 2 * LPR),
                    d = load_stream(r4 + i + 3 * LPR);
