@@ -123,7 +123,17 @@ __global__ __launch_bounds__(kBlock) void absmax_rows_batch(const void* __restri
 __global__ __launch_bounds__(kBlock) void absmax_tensor_batch(const void* __restrict__ plan) {
   const PlanTensor& T = plan_tensors(plan)[blockIdx.x];
   float m = 0.0f;
-  for (int64_t r = threadIdx.x; r < T.t.rows; r += kBlock) m = fmaxf(m, T.t.absmax_row[r]);
+  const float* __restrict__ rm = T.t.absmax_row;
+  const int64_t rows = T.t.rows;
+  int64_t r = threadIdx.x;
+  for (; r + 7 * kBlock < rows; r += 8 * kBlock) {  // eight independent loads in flight
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = rm[r + u * kBlock];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) m = fmaxf(m, v[u]);
+  }
+  for (; r < rows; r += kBlock) m = fmaxf(m, rm[r]);
   m = wave_max(m);
   __shared__ float sm[kBlock / kWave];
   if ((threadIdx.x & (kWave - 1)) == 0) sm[threadIdx.x / kWave] = m;
