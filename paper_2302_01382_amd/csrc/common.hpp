@@ -154,9 +154,6 @@ __device__ __forceinline__ float4 load_stream(const float4* p) {
   const v4f v = __builtin_nontemporal_load((const __attribute__((address_space(1))) v4f*)p);
   return make_float4(v.x, v.y, v.z, v.w);
 }
-__device__ __forceinline__ float load_stream(const float* p) {
-  return __builtin_nontemporal_load((const __attribute__((address_space(1))) float*)p);
-}
 
 // Visits every float4 of x4[0, n4) that the tile round-robin deals to this block: f(value, index).
 template <typename F>

@@ -91,7 +91,8 @@ __global__ __launch_bounds__(kBlock) void fq_rows(const float* __restrict__ x, i
   const QConst c = make_qconst(absmax[r], bits);
   const int64_t base4 = (r * cols) >> 2;
   const float4* x4 = reinterpret_cast<const float4*>(x);
-  for (int64_t i = (c0 >> 2) + lane; i < (c1 >> 2); i += kWave) emit4(load_stream(x4 + base4 + i), c, base4 + i, y, codes, packed);
+  for (int64_t i = (c0 >> 2) + lane; i < (c1 >> 2); i += kWave)
+    emit4(load_stream(x4 + base4 + i), c, base4 + i, y, codes, packed);
 }
 
 // ---- per column: a lane owns 4 adjacent columns; cols % 4 == 0 --------------------------------
