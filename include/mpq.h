@@ -168,6 +168,13 @@ int mpq_quant_error_noalloc(const float* x, int64_t rows, int64_t cols, int gran
  *   gran = MPQ_SWEEP_TENSOR_AND_ROW: both from the same read (twice the arithmetic per element).
  *   fp32 per-lane partial sums, fixed-order double combine: reproducible from call to call.
  *   Workspace from the query (0 for MPQ_PER_ROW), 8-byte aligned.
+ * mpq_calibrate_quant_error_rows_batch: mpq_calibrate_absmax_batch and
+ *   mpq_quant_error_batch(MPQ_PER_ROW) from ONE read of the tensors (the calibration of Sec. 3.1 and
+ *   Eq. 2 with the scales it has just found): absmax_row, absmax_tensor and sse_row are written,
+ *   bit-identical to the two separate calls.  A row of up to 4096 columns stays in registers
+ *   between the two steps; a longer row is read a second time, out of the L2.  No workspace.
+ *   For weights, whose maxima come from the tensor itself; activations whose maxima are running
+ *   ones over several batches take the two separate calls.
  * Errors: MPQ_ERR_NULL / _SHAPE / _ALIGN for a tensor the plan cannot hold (build), MPQ_ERR_SHAPE
  * for a plan_host that is not a built plan, MPQ_ERR_WORKSPACE, MPQ_ERR_GRAN, MPQ_ERR_BITS. */
 typedef struct mpq_sweep_tensor {
@@ -183,6 +190,8 @@ size_t mpq_sweep_plan_bytes(const mpq_sweep_tensor* tensors /* host */, int n_te
 int mpq_sweep_plan_build(const mpq_sweep_tensor* tensors /* host */, int n_tensors, void* plan_host,
                          size_t plan_host_bytes);
 int mpq_calibrate_absmax_batch(const void* plan_host, const void* plan_dev, void* stream);
+int mpq_calibrate_quant_error_rows_batch(const void* plan_host, const void* plan_dev, int b_lo, int b_hi,
+                                         void* stream);
 size_t mpq_quant_error_batch_workspace_bytes(const void* plan_host, int gran, int b_lo, int b_hi);
 int mpq_quant_error_batch(const void* plan_host, const void* plan_dev, int gran, int b_lo, int b_hi,
                           void* ws, size_t ws_bytes, void* stream);

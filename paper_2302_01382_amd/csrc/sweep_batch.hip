@@ -289,6 +289,105 @@ __global__ __launch_bounds__(kBlock) void qe_rows_batch(const void* __restrict__
   }
 }
 
+// ---- max calibration per row AND Eq. 2 per row from ONE read -----------------------------------
+// A row's share of a lane (at most kHold float4: rows up to 1024 columns on 16 lanes, up to 4096 on
+// a wave) stays in registers between the two steps: the row maximum first, then the sweep on the
+// same values.  Longer rows are read a second time; the second read comes out of the L2, which the
+// row has just passed through (the first read is a plain load for that reason, the last one a
+// streaming load).  Lane-to-element assignment and order are those of the two separate kernels, so
+// the results are theirs bit for bit.
+constexpr int kHold = 16;
+
+template <int NB, int LPR>
+__device__ __forceinline__ void calib_qe_rows_of_item(const PlanTensor& T, int index, int b_lo) {
+  constexpr int RG = kBlock / LPR;
+  const int lr = threadIdx.x % LPR;
+  const int e4 = (int)(T.t.cols >> 2);
+  const bool fits = e4 <= kHold * LPR;  // the same for every row of the tensor
+  for (int g = 0; g < kRowGroupsPerItem; ++g) {
+    int64_t r = ((int64_t)index * kRowGroupsPerItem + g) * RG + threadIdx.x / LPR;
+    const bool live = r < T.t.rows;
+    if (!live) r = T.t.rows - 1;  // every lane stays active for the cross-lane steps; result discarded
+    const float4* r4 = reinterpret_cast<const float4*>(T.t.x + r * T.t.cols);
+    float4 v[kHold];
+    float m = 0.0f;
+    if (fits) {
+#pragma unroll
+      for (int u = 0; u < kHold; ++u) {
+        const int i = lr + u * LPR;
+        v[u] = i < e4 ? load_stream(r4 + i) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+      }
+#pragma unroll
+      for (int u = 0; u < kHold; ++u)
+        m = fmaxf(m, fmaxf(fmaxf(fabsf(v[u].x), fabsf(v[u].y)), fmaxf(fabsf(v[u].z), fabsf(v[u].w))));
+    } else {
+      int i = lr;
+      for (; i + 3 * LPR < e4; i += 4 * LPR) {
+        const float4 a = r4[i], b = r4[i + LPR], c = r4[i + 2 * LPR], d = r4[i + 3 * LPR];
+        m = fmaxf(m, fmaxf(fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))),
+                           fmaxf(fmaxf(fabsf(b.x), fabsf(b.y)), fmaxf(fabsf(b.z), fabsf(b.w)))));
+        m = fmaxf(m, fmaxf(fmaxf(fmaxf(fabsf(c.x), fabsf(c.y)), fmaxf(fabsf(c.z), fabsf(c.w))),
+                           fmaxf(fmaxf(fabsf(d.x), fabsf(d.y)), fmaxf(fabsf(d.z), fabsf(d.w)))));
+      }
+      for (; i < e4; i += LPR) {
+        const float4 a = r4[i];
+        m = fmaxf(m, fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))));
+      }
+    }
+    if (LPR == 16) {  // every lane of the row group ends up with the row's maximum
+      m = fmaxf(m, dpp<kQuadSwap1>(m));
+      m = fmaxf(m, dpp<kQuadSwap2>(m));
+      m = fmaxf(m, dpp<kRowHalfMirror>(m));
+      m = fmaxf(m, dpp<kRowMirror>(m));
+    } else {
+      m = wave_max(m);
+    }
+    if (lr == 0 && live) T.t.absmax_row[r] = m;
+    float mine;
+    {
+      const int j = lr < 7 ? lr : lr - 7;
+      float sc, inv;
+      bit_constants(m, b_lo + (j < NB ? j : 0), sc, inv);
+      mine = lr < 7 ? inv : sc;
+    }
+    Sweep<NB> s;
+    s.m = m;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      s.inv[b] = __shfl(mine, b, LPR);
+      s.sc[b] = __shfl(mine, 7 + b, LPR);
+      s.acc[b] = 0.0f;
+    }
+    if (fits) {
+#pragma unroll
+      for (int u = 0; u < kHold; ++u)
+        if (lr + u * LPR < e4) s.add4(v[u]);
+    } else {
+      int i = lr;
+      for (; i + 3 * LPR < e4; i += 4 * LPR) {
+        const float4 a = load_stream(r4 + i), b = load_stream(r4 + i + LPR), c = load_stream(r4 + i + 2 * LPR),
+                     d = load_stream(r4 + i + 3 * LPR);
+        s.add4(a); s.add4(b); s.add4(c); s.add4(d);
+      }
+      for (; i < e4; i += LPR) s.add4(load_stream(r4 + i));
+    }
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      const float w = LPR == 16 ? row16_sum(s.acc[b]) : wave_sum(s.acc[b]);
+      if (lr == 0 && live) T.t.sse_row[r * NB + b] = (double)w;
+    }
+  }
+}
+
+template <int NB>
+__global__ __launch_bounds__(kBlock) void calib_qe_rows_batch(const void* __restrict__ plan, int b_lo) {
+  const PlanHeader* H = reinterpret_cast<const PlanHeader*>(plan);
+  const PlanItem it = (plan_flat_items(plan, H->n_tensors) + H->n_flat_items)[blockIdx.x];
+  const PlanTensor& T = plan_tensors(plan)[it.tensor];
+  if (T.lanes_per_row == 16) calib_qe_rows_of_item<NB, 16>(T, it.index, b_lo);
+  else calib_qe_rows_of_item<NB, 64>(T, it.index, b_lo);
+}
+
 template <int NB>
 static void launch_qe_batch(const PlanHeader* H, const void* plan_dev, int gran, int b_lo, double* ws,
                             hipStream_t st) {
@@ -432,5 +531,30 @@ extern "C" int mpq_quant_error_batch(const void* plan_host, const void* plan_dev
     case 6: launch_qe_batch<6>(H, plan_dev, gran, b_lo, wsd, st); break;
     default: launch_qe_batch<7>(H, plan_dev, gran, b_lo, wsd, st); break;
   }
+  return launch_status();
+}
+
+extern "C" int mpq_calibrate_quant_error_rows_batch(const void* plan_host, const void* plan_dev, int b_lo, int b_hi,
+                                                    void* stream) {
+  if (!plan_host || !plan_dev) return MPQ_ERR_NULL;
+  const PlanHeader* H = checked_plan(plan_host);
+  if (!H) return MPQ_ERR_SHAPE;
+  if (reinterpret_cast<uintptr_t>(plan_dev) & 7u) return MPQ_ERR_ALIGN;
+  if (b_lo < 2 || b_hi > 8 || b_lo > b_hi) return MPQ_ERR_BITS;
+  const PlanTensor* T = plan_tensors(plan_host);
+  for (int i = 0; i < H->n_tensors; ++i)
+    if (!T[i].t.sse_row) return MPQ_ERR_NULL;
+  hipStream_t st = (hipStream_t)stream;
+  const unsigned grid = (unsigned)H->n_row_items;
+  switch (b_hi - b_lo + 1) {
+    case 1: calib_qe_rows_batch<1><<<grid, kBlock, 0, st>>>(plan_dev, b_lo); break;
+    case 2: calib_qe_rows_batch<2><<<grid, kBlock, 0, st>>>(plan_dev, b_lo); break;
+    case 3: calib_qe_rows_batch<3><<<grid, kBlock, 0, st>>>(plan_dev, b_lo); break;
+    case 4: calib_qe_rows_batch<4><<<grid, kBlock, 0, st>>>(plan_dev, b_lo); break;
+    case 5: calib_qe_rows_batch<5><<<grid, kBlock, 0, st>>>(plan_dev, b_lo); break;
+    case 6: calib_qe_rows_batch<6><<<grid, kBlock, 0, st>>>(plan_dev, b_lo); break;
+    default: calib_qe_rows_batch<7><<<grid, kBlock, 0, st>>>(plan_dev, b_lo); break;
+  }
+  absmax_tensor_batch<<<(unsigned)H->n_tensors, kBlock, 0, st>>>(plan_dev);
   return launch_status();
 }

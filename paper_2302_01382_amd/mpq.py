@@ -24,6 +24,7 @@ EXPORTS = [
     "mpq_quant_error", "mpq_quant_error_noalloc", "mpq_noise_inject",
     "mpq_eqe", "mpq_eqe_channels", "mpq_hutchinson_trace", "mpq_latency_estimate", "mpq_model_size_bytes",
     "mpq_sweep_plan_bytes", "mpq_sweep_plan_build", "mpq_calibrate_absmax_batch",
+    "mpq_calibrate_quant_error_rows_batch",
     "mpq_quant_error_batch_workspace_bytes", "mpq_quant_error_batch", "mpq_qgemm_workspace_bytes", "mpq_qgemm",
     "mpq_sse_pair_workspace_bytes", "mpq_sse_pair", "mpq_qgemm_score_workspace_bytes", "mpq_qgemm_score",
     "mpq_search_bisection", "mpq_search_greedy", "mpq_noise_inject_sweep",
@@ -87,6 +88,7 @@ def lib():
         L.mpq_sweep_plan_bytes.argtypes = [vp, ci]
         L.mpq_sweep_plan_build.argtypes = [vp, ci, vp, sz]
         L.mpq_calibrate_absmax_batch.argtypes = [vp, vp, vp]
+        L.mpq_calibrate_quant_error_rows_batch.argtypes = [vp, vp, ci, ci, vp]
         L.mpq_quant_error_batch_workspace_bytes.restype = sz
         L.mpq_quant_error_batch_workspace_bytes.argtypes = [vp, ci, ci, ci]
         L.mpq_quant_error_batch.argtypes = [vp, vp, ci, ci, ci, vp, sz, vp]
@@ -390,6 +392,13 @@ def sweep_plan_build(tensors, b_lo=2, b_hi=8) -> "SweepPlan":
 def calibrate_absmax_batch(plan: "SweepPlan"):
     """Row maxima and tensor maxima of every tensor of the plan; results in plan.absmax_row / absmax_tensor."""
     _check(lib().mpq_calibrate_absmax_batch(plan.host, plan.dev.data_ptr(), _stream()), "mpq_calibrate_absmax_batch")
+    return plan
+
+
+def calibrate_quant_error_rows_batch(plan: "SweepPlan"):
+    """Row and tensor maxima AND the per-row error sums of every tensor of the plan from one read."""
+    _check(lib().mpq_calibrate_quant_error_rows_batch(plan.host, plan.dev.data_ptr(), plan.b_lo, plan.b_hi, _stream()),
+           "mpq_calibrate_quant_error_rows_batch")
     return plan
 
 

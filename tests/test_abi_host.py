@@ -383,6 +383,16 @@ def test_sweep_batch_call_validation():
     nost = (mpq.SweepTensor * 1)(_sweep_desc(st=0))
     assert L.mpq_sweep_plan_build(nost, 1, buf, n) == mpq.OK
     assert f(buf, FAKE16, mpq.PER_TENSOR, 2, 8, FAKE16, 1 << 20, None) == mpq.ERR_NULL
+    # the one-read form of calibration + per-row sums
+    g = L.mpq_calibrate_quant_error_rows_batch
+    assert g(junk, FAKE16, 2, 8, None) == mpq.ERR_SHAPE
+    assert g(buf, None, 2, 8, None) == mpq.ERR_NULL
+    assert g(buf, C.c_void_p(0x10004), 2, 8, None) == mpq.ERR_ALIGN
+    assert g(buf, FAKE16, 1, 8, None) == mpq.ERR_BITS
+    assert g(buf, FAKE16, 5, 4, None) == mpq.ERR_BITS
+    nosr = (mpq.SweepTensor * 1)(_sweep_desc(sr=0))
+    assert L.mpq_sweep_plan_build(nosr, 1, buf, n) == mpq.OK
+    assert g(buf, FAKE16, 2, 8, None) == mpq.ERR_NULL
 
 
 @needs_no_gpu
