@@ -147,6 +147,13 @@ def test_config4_all_96_tensors_batched_sweep_at_both_granularities():
     mpq.quant_error_batch(plan, mpq.PER_ROW)
     am_r, am_t = host(plan.absmax_row_all), host(plan.absmax_tensor_all)
     sse_t, sse_r = host(plan.sse_tensor_all), host(plan.sse_row_all)
+    # the same maxima and per-row sums from ONE read (what the oracle checks below it checks for both)
+    for t in (plan.absmax_row_all, plan.absmax_tensor_all, plan.sse_row_all):
+        t.fill_(-1.0)
+    mpq.calibrate_quant_error_rows_batch(plan)
+    np.testing.assert_array_equal(host(plan.absmax_row_all), am_r)
+    np.testing.assert_array_equal(host(plan.absmax_tensor_all), am_t)
+    np.testing.assert_array_equal(host(plan.sse_row_all), sse_r)
 
     def one(w):
         mt, mr = oracle.absmax(w), oracle.absmax(w, oracle.PER_ROW)
