@@ -5,8 +5,11 @@ Default (`--workload headline`): both halves of the metric on their own workload
   sweep  configuration 4, the sensitivity sweep over the 96 BERT-large weight tensors (302 M
          elements, 1.208 GB): a step = max calibration per output channel and per tensor, then the
          error sums of b = 2..8 per tensor and per output channel, all through the batched calls
-         (5 launches).  `value` = 12 bytes per element (three reads of 4 bytes) / time.  The seven
-         noise levels per tensor are timed separately and reported separately.
+         (5 launches).  `value` = 12 bytes per element (three reads of 4 bytes) / time; 100 timed
+         steps after 60 warm-up steps by default (a step is 0.6 ms and the chip needs some 15 ms of
+         work to leave its idle clocks).  Reported beside it: the same results from two reads
+         (calibration and the per-row sums from one read), both granularities from one read, and
+         the seven noise levels per tensor.
   gemm   mpq_qgemm on every configured GEMM shape (configurations 2, 3, 5; int8 and packed int4
          weights), cold operands: TOP/s, fraction of the int8 matrix peak and of the shape's own
          roofline.
