@@ -216,6 +216,29 @@ def test_sse_brute_force_closed_form_and_invariances():
 
 
 
+def test_two_bit_error_is_the_distance_to_the_nearest_of_minus_m_zero_m():
+    """For b = 2 the grid of Eq. 1 is {-m, 0, +m} (qmax = 1, step = m): the error of an element is
+    its distance to the nearest of the three points, min(|x|, ||x| - m|), also for |x| > m (the clip)
+    and for m = 0.  Independent of the rounding recipe, so it pins the two-bit column of Eq. 2's sum;
+    the library's sweep kernels use exactly this form for two bits."""
+    r = rng(37)
+    for shape, m_scale in (((53, 67), 1.0), ((40, 33), 0.5), ((9, 11), 0.0)):
+        x = r.standard_normal(shape).astype(np.float32)
+        x.ravel()[:5] = [0.0, 1.0, -1.0, 0.5, -0.5]
+        m = (oracle.absmax(x) * np.float32(m_scale)).astype(np.float32)   # own maximum, a foreign smaller one, zero
+        mm = float(m[0])
+        x.ravel()[5:8] = [mm / 2, -mm / 2, mm]                             # the midpoints (ties) and the grid point itself
+        a = np.abs(x.astype(np.float64))
+        want = math.fsum((np.minimum(a, np.abs(a - mm)) ** 2).ravel().tolist())
+        got = oracle.quant_error(x, m, 2, 2)[0, 0]
+        assert abs(got - want) <= 1e-12 * max(want, 1e-300)
+        # per row, with each row's own maximum
+        mr = oracle.absmax(x, oracle.PER_ROW)
+        want_r = [math.fsum((np.minimum(np.abs(row.astype(np.float64)), np.abs(np.abs(row.astype(np.float64)) - float(k))) ** 2).tolist())
+                  for row, k in zip(x, mr)]
+        np.testing.assert_allclose(oracle.quant_error(x, mr, 2, 2, oracle.PER_ROW)[:, 0], want_r, rtol=1e-12, atol=0)
+
+
 def test_sse_of_a_tensor_lying_on_the_grid():
     """Eq. 2 is stated over the reals: Q_b(x) inside the sum is the grid point code * scale_b itself.
     A tensor whose every element is such a grid point therefore has SSE_b == 0 exactly.  With a
