@@ -525,6 +525,13 @@ def _timed_calls(torch, calls, reps):
     return out
 
 
+# HBM traffic per launch of mpq_qgemm on cfg5.ffn2 (16384 x 4096 x 1024), bytes, from the counter runs
+# summarised in profiles/cfg5_ffn2_qgemm_hbm_traffic.txt: (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000) KiB
+TRAFFIC_BYTES_PER_LAUNCH_GEMM = {
+    ("cfg5.ffn2", 8): (49275.3 * 2.0 + 67481.8) * 1024.0,
+    ("cfg5.ffn2", 4): (41118.6 * 2.0 + 66957.9) * 1024.0,
+}
+
 # HBM traffic per launch of the batched sweep kernels over configuration 4, bytes, from the rocprofv3
 # counter runs summarised in profiles/cfg4_batched_sweep_hbm_traffic.txt (FETCH_SIZE and WRITE_SIZE
 # scaled by what the same counters read for a plain device copy of known size in the same run).
@@ -673,7 +680,8 @@ def bench_gemm_block(torch, mpq, workloads, peaks):
                                   "all_shapes_together": round(sum(r["us"] for r in rows[1::2]) / sum(r["us"] for r in rows[0::2]), 3)},
         "shapes": rows,
         "roofline": {"bound": "mfma", "achieved": best["tops"], "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
-                     "frac": best["tops"] / INT8_PEAK_TOPS, "traffic": None, "bar": 0.60,
+                     "frac": best["tops"] / INT8_PEAK_TOPS,
+                     "traffic": TRAFFIC_BYTES_PER_LAUNCH_GEMM.get((best["shape"], best["w_storage_bits"])), "bar": 0.60,
                      "kernel": "qgemm %s W%d (%d x %d x %d)" % (best["shape"], best["w_storage_bits"], best["M"], best["K"], best["N"]),
                      "algorithmic_per_launch": 2.0 * best["M"] * best["N"] * best["K"], "avg_launch_us": best["us"],
                      "frac_of_measured_mfma_rate_random_bytes": best["tops"] / peaks["int8_mfma_tops_random_bytes"]},
@@ -1005,11 +1013,24 @@ def measured_peaks(torch, mpq):
     return out
 
 
+def calibrate_copy(torch):
+    """A plain device copy of known size (225792 KiB read, as many written), three times: what the
+    FETCH_SIZE / WRITE_SIZE readings of a counter run are scaled by."""
+    src = torch.empty(225792 * 256, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    del src, dst
+
+
 def run_gemm_shapes(torch, mpq, workloads, args):
     """mpq_qgemm on every configured GEMM shape (configurations 2, 3 and 5, int8 and packed int4
     weights, per-output-channel scales, fp32 output), operands rotated through more than the
     memory-side cache holds: time per launch, TOP/s, fraction of the int8 matrix peak, and
     fraction of the shape's own roofline min(matrix peak, arithmetic intensity x HBM peak)."""
+    if args.calibrate_copy:
+        calibrate_copy(torch)
     rows = gemm_shape_rows(workloads, only=args.shape)
     best = max(rows, key=lambda r: r["tops"])
     peaks = measured_peaks(torch, mpq)
@@ -1024,7 +1045,8 @@ def run_gemm_shapes(torch, mpq, workloads, args):
         "dtype": "int8 x int8 -> int32, fp32 epilogue", "data": "synthetic",
         "config": {"workload": "gemm: the %d GEMM shapes of configurations 2, 3 and 5, int8 and packed int4 weights" % (len(rows) // 2)},
         "roofline": {"bound": "mfma", "achieved": best["tops"], "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
-                     "frac": best["tops"] / INT8_PEAK_TOPS, "traffic": None,
+                     "frac": best["tops"] / INT8_PEAK_TOPS,
+                     "traffic": TRAFFIC_BYTES_PER_LAUNCH_GEMM.get((best["shape"], best["w_storage_bits"])),
                      "kernel": "qgemm %s W%d" % (best["shape"], best["w_storage_bits"]), "avg_launch_us": best["us"]},
         "measured_peaks": peaks,
         "shapes": rows,
@@ -1101,12 +1123,7 @@ def main():
         return
     if args.workload == "sweep":   # the sweep block of the default run alone (what the counter passes profile)
         if args.calibrate_copy:
-            src = torch.empty(225792 * 256, dtype=torch.float32, device="cuda")   # 225792 KiB
-            dst = torch.empty_like(src)
-            for _ in range(3):
-                dst.copy_(src)
-            torch.cuda.synchronize()
-            del src, dst
+            calibrate_copy(torch)
         sweep, _ = bench_sweep_cfg4(torch, mpq, workloads, args.steps, args.warmup)
         roof = sweep.pop("roofline")
         print(json.dumps({"metric": METRIC, "value": sweep["gbs"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
