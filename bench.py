@@ -39,6 +39,7 @@ Other workloads (the parity-test configurations, measured with the same machiner
     gemm    mpq_qgemm on every configured GEMM shape: TOP/s, fraction of the matrix peak and of the
             shape's own roofline
     hutchinson  Hessian-trace probe (random sign vectors, quadratic forms on the fp32 matrix cores)
+    kernels every streaming call of the path (a1, a2, a3, a4, a6) on one 268 MB tensor, cold: GB/s each
 All inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 """
 from __future__ import annotations
@@ -1054,6 +1055,72 @@ def run_gemm_shapes(torch, mpq, workloads, args):
     print(json.dumps(out))
 
 
+def run_kernels(torch, mpq, workloads, args):
+    """Every streaming call of the path on ONE large tensor (16384 x 4096 fp32 = 268 MB, the hidden
+    activation of configuration 5; five copies rotated so that the 256 MB memory-side cache is cold):
+    microseconds per call (main kernel plus finishing kernel where there is one), algorithmic GB/s
+    and the fraction of the HBM peak.  Best of three rounds of 20 back-to-back calls after six warm-up
+    calls."""
+    R, Cc, NBUF = 16384, 4096, 5
+    n = R * Cc
+    g = torch.Generator(device="cuda").manual_seed(11)
+    xs = [torch.randn(R, Cc, device="cuda", generator=g) for _ in range(NBUF)]
+    am_t = mpq.calibrate_absmax(xs[0])
+    am_r = mpq.calibrate_absmax(xs[0], mpq.PER_ROW)
+    y = torch.empty(R, Cc, device="cuda")
+    codes = torch.empty(R, Cc, dtype=torch.int8, device="cuda")
+    packed = torch.empty(R, Cc // 2, dtype=torch.uint8, device="cuda")
+    out_t, out_r = torch.empty(1, device="cuda"), torch.empty(R, device="cuda")
+    qe_t = torch.empty((1, 7), dtype=torch.float64, device="cuda")
+    qe_r = torch.empty((R, 7), dtype=torch.float64, device="cuda")
+    ws = mpq.Workspace()
+    cases = [   # name, scope-table row, algorithmic bytes per element, call
+        ("calibrate_absmax per tensor", "a1", 4.0, lambda i: mpq.calibrate_absmax(xs[i % NBUF], out=out_t, ws=ws)),
+        ("calibrate_absmax per row", "a1", 4.0, lambda i: mpq.calibrate_absmax(xs[i % NBUF], mpq.PER_ROW, out=out_r, ws=ws)),
+        ("fake_quant -> fp32", "a2", 8.0, lambda i: mpq.fake_quant(xs[i % NBUF], am_t, 8, y=y)),
+        ("fake_quant -> int8 codes", "a2", 5.0,
+         lambda i: mpq.fake_quant(xs[i % NBUF], am_t, 8, want_y=False, want_codes=True, codes=codes)),
+        ("fake_quant -> packed int4", "a2", 4.5,
+         lambda i: mpq.fake_quant(xs[i % NBUF], am_t, 4, want_y=False, want_packed4=True, packed4=packed)),
+        ("fake_quant per row -> int8 codes", "a2", 5.0,
+         lambda i: mpq.fake_quant(xs[i % NBUF], am_r, 8, mpq.PER_ROW, want_y=False, want_codes=True, codes=codes)),
+        ("quant_error b = 2..8 per tensor", "a3", 4.0, lambda i: mpq.quant_error(xs[i % NBUF], am_t, out=qe_t, ws=ws)),
+        ("quant_error b = 2..8 per row", "a3", 4.0,
+         lambda i: mpq.quant_error(xs[i % NBUF], am_r, gran=mpq.PER_ROW, out=qe_r, ws=ws)),
+        ("noise_inject, one level", "a4", 8.0, lambda i: mpq.noise_inject(xs[i % NBUF], am_t, 4, LAMBDA, 1, 2, out=y)),
+        ("sse_pair", "a6", 8.0, lambda i: mpq.sse_pair(xs[i % NBUF], xs[(i + 1) % NBUF])),
+    ]
+    rows = []
+    for name, row, bpe, fn in cases:
+        for i in range(6):
+            fn(i)
+        torch.cuda.synchronize()
+        best = None
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(20):
+                fn(i)
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / 20
+            best = us if best is None or us < best else best
+        rows.append({"call": name, "row": row, "us": round(best, 2), "bytes_per_element": bpe,
+                     "gbs": round(bpe * n / best / 1e3, 1), "frac_of_hbm_peak": round(bpe * n / best / 1e3 / HBM_PEAK_GBS, 4)})
+    slow = min(rows, key=lambda r: r["frac_of_hbm_peak"])
+    total_bytes = sum(r["bytes_per_element"] for r in rows) * n
+    total_us = sum(r["us"] for r in rows)
+    print(json.dumps({
+        "metric": "streaming calls of the path on one 268 MB tensor, algorithmic GB/s", "value": total_bytes / total_us / 1e3,
+        "unit": "GB/s", "n_gpus": 1, "steps": 20, "warmup": 6, "ms_per_step": total_us / 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "kernels: a1, a2, a3, a4, a6 on one 16384 x 4096 fp32 tensor, five copies rotated (cold memory-side cache)"},
+        "roofline": {"bound": "hbm", "achieved": slow["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": slow["frac_of_hbm_peak"], "traffic": None, "kernel": slow["call"], "bar": 0.70,
+                     "algorithmic_per_launch": slow["bytes_per_element"] * n, "avg_launch_us": slow["us"]},
+        "calls": rows}))
+
+
 def run_latency(torch, mpq, workloads, args):
     """Kernel latency table of mpq_qgemm at inference batch size one (the configured ResNet-50 and
     BERT-base layer shapes with M divided by their batch of 32) and the relative latency /
@@ -1089,7 +1156,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=None,
                     help="untimed steps before them (default: 60 for the sweep workloads: from idle the chip needs "
                          "some 15 ms of work before its clocks are up, and the first 20 steps run 15 %% slower; 3 otherwise)")
-    ap.add_argument("--workload", choices=["cfg2", "cfg3", "cfg4", "cfg4-1stream", "cfg4-unfused", "cfg5", "cfg5-twopass", "cfg5-unfused", "search", "latency", "hutchinson", "gemm", "headline", "sweep"], default="headline")
+    ap.add_argument("--workload", choices=["cfg2", "cfg3", "cfg4", "cfg4-1stream", "cfg4-unfused", "cfg5", "cfg5-twopass", "cfg5-unfused", "search", "latency", "hutchinson", "gemm", "headline", "sweep", "kernels"], default="headline")
     ap.add_argument("--shape", default=None, help="gemm: only this configured shape, as MxKxN (e.g. 16384x4096x1024)")
     ap.add_argument("--cpu-sample-rows", type=int, default=2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -1137,6 +1204,9 @@ def main():
         return
     if args.workload == "latency":
         run_latency(torch, mpq, workloads, args)
+        return
+    if args.workload == "kernels":
+        run_kernels(torch, mpq, workloads, args)
         return
     if args.workload == "hutchinson":
         run_hutchinson(torch, mpq, workloads, args)
