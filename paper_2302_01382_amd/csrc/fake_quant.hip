@@ -91,8 +91,17 @@ __global__ __launch_bounds__(kBlock) void fq_rows(const float* __restrict__ x, i
   const QConst c = make_qconst(absmax[r], bits);
   const int64_t base4 = (r * cols) >> 2;
   const float4* x4 = reinterpret_cast<const float4*>(x);
-  for (int64_t i = (c0 >> 2) + lane; i < (c1 >> 2); i += kWave)
-    emit4(load_stream(x4 + base4 + i), c, base4 + i, y, codes, packed);
+  int64_t i = (c0 >> 2) + lane;
+  const int64_t end = c1 >> 2;
+  for (; i + 3 * kWave < end; i += 4 * kWave) {  // four loads in flight per lane
+    const float4 v0 = load_stream(x4 + base4 + i), v1 = load_stream(x4 + base4 + i + kWave),
+                 v2 = load_stream(x4 + base4 + i + 2 * kWave), v3 = load_stream(x4 + base4 + i + 3 * kWave);
+    emit4(v0, c, base4 + i, y, codes, packed);
+    emit4(v1, c, base4 + i + kWave, y, codes, packed);
+    emit4(v2, c, base4 + i + 2 * kWave, y, codes, packed);
+    emit4(v3, c, base4 + i + 3 * kWave, y, codes, packed);
+  }
+  for (; i < end; i += kWave) emit4(load_stream(x4 + base4 + i), c, base4 + i, y, codes, packed);
 }
 
 // ---- per column: a lane owns 4 adjacent columns; cols % 4 == 0 --------------------------------
