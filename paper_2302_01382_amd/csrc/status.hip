@@ -25,6 +25,6 @@ const char* mpq_strerror(int status) {
 
 int mpq_last_hip_error(void) { return mpq::g_last_hip_error; }
 
-int mpq_version(void) { return 100; }
+int mpq_version(void) { return 102; }  // 1.2: batched sweep calls, host functions, no-allocation sweep
 
 }  // extern "C"
