@@ -327,7 +327,7 @@ static int run_qgemm(const int8_t* a_q, const void* w_q, int w_storage_bits, int
       d.acc_out = planes;
       d.split = sp.split;
       d.k_per_split = sp.k_per_split;
-      const int rc = launch_dma_64(w4, d);
+      const int rc = launch_dma_64(w4, false, d);
       if (rc != MPQ_OK) return rc;
       const int64_t MN = M * N;
       const bool vec = (N & 3) == 0 && (!y_out || aligned16(y_out)) && (!acc_out || aligned16(acc_out)) &&
@@ -351,7 +351,9 @@ static int run_qgemm(const int8_t* a_q, const void* w_q, int w_storage_bits, int
     if (N % 192 == 0 && t192 <= kNumCU && t192 >= kNumCU * 3 / 4 && t192 * 192 * 192 <= M * N + M * N / 32)
       return launch_dma_192(w4, K >= 1024, d);
     if (N > 64 && tiles(128, 128) >= kNumCU / 2) return launch_dma_128(w4, K >= 2048 || tiles(128, 128) <= kNumCU, d);
-    return launch_dma_64(w4, d);
+    // k tiles of 256 bytes where the grid is at most one workgroup per CU anyway (the longer stages
+    // leave room for one workgroup per CU only) and k is long enough to have several of them
+    return launch_dma_64(w4, K >= 1024 && tiles(64, 64) <= kNumCU, d);
   }
   const dim3 grid((unsigned)gx, (unsigned)gy);
   if (w4) qgemm_k<true><<<grid, kGemmThreads, 0, st>>>(a_q, w_q, M, N, K, a_scale, w_scale, per_row, y_out, acc_out, epi);
@@ -375,7 +377,8 @@ extern "C" int mpq_init(void) {
     if (rc == MPQ_OK) rc = launch_dma_192(w4 != 0, false, d);
     if (rc == MPQ_OK) rc = launch_dma_128(w4 != 0, true, d);
     if (rc == MPQ_OK) rc = launch_dma_128(w4 != 0, false, d);
-    if (rc == MPQ_OK) rc = launch_dma_64(w4 != 0, d);
+    if (rc == MPQ_OK) rc = launch_dma_64(w4 != 0, false, d);
+    if (rc == MPQ_OK) rc = launch_dma_64(w4 != 0, true, d);
     if (rc != MPQ_OK) return rc;
   }
   return MPQ_OK;

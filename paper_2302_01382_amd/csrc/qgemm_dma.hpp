@@ -124,16 +124,17 @@ __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N_) : "memory");
 }
 
-// KB: k bytes per stage (128 or 64)
+// KB: k bytes per stage (64, 128 or 256)
 template <int BM, int BN, int WM, int WN, int NSTAGE, bool W4, int KB>
 struct DmaCfg {
   static constexpr int DBK = KB;
-  static constexpr int CPR = KB / 16;                 // 16-byte chunks per int8 tile row (8 | 4)
-  static constexpr int RPI = 64 / CPR;                // tile rows one wave-load covers (8 | 16)
-  static constexpr int SH = CPR == 8 ? 1 : 2;         // swizzle: slot = chunk ^ ((row >> SH) & (CPR-1))
-  static constexpr int PCPR = KB / 32;                // 16-byte chunks per packed-int4 tile row (4 | 2)
-  static constexpr int PRPI = 64 / PCPR;              // packed rows per wave-load (16 | 32)
-  static constexpr int PSH = PCPR == 4 ? 2 : 3;
+  static constexpr int CPR = KB / 16;                 // 16-byte chunks per int8 tile row (4 | 8 | 16)
+  static constexpr int RPI = 64 / CPR;                // tile rows one wave-load covers (16 | 8 | 4)
+  // swizzle: slot = chunk ^ ((row >> SH) & (CPR-1)); 2^SH rows share 256 bytes (one sweep of the banks)
+  static constexpr int SH = CPR == 16 ? 0 : CPR == 8 ? 1 : 2;
+  static constexpr int PCPR = KB / 32;                // 16-byte chunks per packed-int4 tile row (2 | 4 | 8)
+  static constexpr int PRPI = 64 / PCPR;              // packed rows per wave-load (32 | 16 | 8)
+  static constexpr int PSH = PCPR == 8 ? 1 : PCPR == 4 ? 2 : 3;
   static constexpr int NW = WM * WN;
   static constexpr int NT = NW * 64;
   static constexpr int TM = BM / WM, TN = BN / WN;   // per-wave tile
@@ -149,7 +150,7 @@ struct DmaCfg {
   static constexpr int LPW = (NLA + NLB) / NW;        // wave-loads per wave per stage
   static_assert(NLA % NW == 0 && NLB % NW == 0, "loads must divide evenly over the waves");
   static_assert(TM % 32 == 0 && TN % 32 == 0, "wave tile is a multiple of 32 x 32");
-  static_assert(KB == 128 || KB == 64, "k tile of 128 or 64 bytes");
+  static_assert(KB == 256 || KB == 128 || KB == 64, "k tile of 64, 128 or 256 bytes");
   static_assert((NSTAGE - 1) * LPW < 64, "vmcnt is a 6-bit counter");
 };
 
@@ -715,6 +716,6 @@ struct DmaArgs {
 int launch_dma_256(bool w4, const DmaArgs& a);
 int launch_dma_192(bool w4, bool three_stages, const DmaArgs& a);
 int launch_dma_128(bool w4, bool three_stages, const DmaArgs& a);
-int launch_dma_64(bool w4, const DmaArgs& a);
+int launch_dma_64(bool w4, bool long_k, const DmaArgs& a);
 
 }  // namespace mpq

@@ -433,10 +433,10 @@ def test_qgemm_score_small_shapes(mnk, wbits):
 
 @pytest.mark.parametrize("mnk,wbits", [((2048, 2048, 384), 8), ((4100, 4092, 160), 4), ((2085, 2046, 112), 8),
                                         ((300, 200, 1152), 4), ((1568, 512, 1024), 8), ((6272, 256, 512), 4),
-                                        ((12288, 768, 128), 8)])
+                                        ((12288, 768, 128), 8), ((130, 70, 1296), 8), ((100, 200, 2080), 4)])
 def test_qgemm_score_every_tile_size(mnk, wbits):
-    """Shapes that select the 64, 128 and 256 tiles, with ragged edges, N not a multiple of 4 and
-    several tiles per workgroup; the whole product is small enough for the oracle."""
+    """Shapes that select the 64 (k tiles of 128 and of 256 bytes), 128 and 256 tiles, with ragged edges, N
+    not a multiple of 4 and several tiles per workgroup; the whole product is small enough for the oracle."""
     M, N, K = mnk
     a, ws, sa, sw, y_o, y_ref, want = score_case(M, N, K, wbits, mpq.PER_ROW, 50)
     da, dw, dsa, dsw, dref = dev(a), dev(ws), dev(sa), dev(sw), dev(y_ref)
@@ -457,7 +457,7 @@ def test_qgemm_score_every_tile_size(mnk, wbits):
 # ------------------------------------------------------------------- qgemm + activation + absmax
 @pytest.mark.parametrize("mnk,wbits", [((64, 256, 256), 8), ((33, 31, 130), 8), ((300, 70, 48), 4), ((2048, 2048, 384), 8),
                                         ((4100, 4092, 160), 4), ((2085, 2046, 112), 8), ((6272, 256, 512), 4),
-                                        ((12288, 768, 128), 4)])
+                                        ((12288, 768, 128), 4), ((130, 70, 1296), 8), ((100, 200, 2080), 4)])
 @pytest.mark.parametrize("act", [1, 2])
 def test_qgemm_act_matches_the_composition(mnk, wbits, act):
     M, N, K = mnk
@@ -491,7 +491,7 @@ def test_qgemm_act_matches_the_composition(mnk, wbits, act):
 # ------------------------------------------------------- qgemm + activation + Eq. 1 in the epilogue
 @pytest.mark.parametrize("mnk,wbits", [((64, 256, 256), 8), ((33, 31, 130), 8), ((300, 70, 48), 4), ((2048, 2048, 384), 8),
                                         ((4100, 4092, 160), 4), ((2085, 2046, 112), 8), ((6272, 256, 512), 4),
-                                        ((12288, 768, 128), 4)])
+                                        ((12288, 768, 128), 4), ((130, 70, 1296), 8), ((100, 200, 2080), 4)])
 @pytest.mark.parametrize("act,bits", [(0, 8), (1, 8), (1, 4), (2, 8), (2, 4), (2, 2)])
 def test_qgemm_act_codes_are_the_fake_quant_codes_of_the_activated_output(mnk, wbits, act, bits):
     """Two passes over the product: the calibration-only pass must find the absmax the storing pass
