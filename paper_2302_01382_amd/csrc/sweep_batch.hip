@@ -14,6 +14,8 @@
 // The arithmetic per element is the one of the single-tensor calls (sweep.hpp); per-row results
 // are bit-identical to mpq_quant_error(MPQ_PER_ROW), per-tensor sums differ from
 // mpq_quant_error(MPQ_PER_TENSOR) by the rounding of a different summation order.
+// Where the maxima come from the swept tensors themselves (weights), one more call takes the row
+// maxima and the per-row sums from the same read (calib_qe_rows_batch).
 #include "common.hpp"
 #include "sweep.hpp"
 
