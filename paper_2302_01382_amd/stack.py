@@ -161,6 +161,30 @@ class QuantStack:
             out.append(mpq.eqe(float(sse.item()), w.numel(), float(am.item())))
         return out
 
+    def noise_sensitivity(self, b: int, lam: float = 0.28867513, seed: int = 0) -> List[float]:
+        """E_N of Sec. 3.2.2 (Eq. 3-5) on this stack: for every layer, the drop of the score when
+        Gaussian noise with the spread of b-bit rounding (sigma = lam * step_b, mpq_noise_inject) is
+        added to that layer's weights alone, all layers otherwise at the widest listed width.  The
+        noisy weights go through the same quantizer as the clean ones (widest width), into the
+        layer's code buffer, which is restored afterwards; layer l draws from noise stream l."""
+        top = max(self.bit_widths)
+        base = self.evaluate([top] * len(self.weights))
+        out = []
+        for l, w in enumerate(self.weights):
+            codes, scale, store = self.w_q[l][top]
+            keep_codes, keep_scale = codes.clone(), scale.clone()
+            noisy = mpq.noise_inject(w, self.w_absmax[l], b, lam, seed, l, self.w_gran)
+            am = mpq.calibrate_absmax(noisy, self.w_gran, ws=self.ws)
+            if store == 8:
+                mpq.fake_quant(noisy, am, top, self.w_gran, want_y=False, codes=codes)
+            else:
+                mpq.fake_quant(noisy, am, top, self.w_gran, want_y=False, want_packed4=True, packed4=codes)
+            mpq.scale_from_absmax(am, top, out=scale)
+            out.append(base - self.evaluate([top] * len(self.weights)))
+            codes.copy_(keep_codes)
+            scale.copy_(keep_scale)
+        return out
+
     def order_by(self, sensitivity: Sequence[float]) -> List[int]:
         """Layer ids in ascending order of sensitivity (ties: lower id first)."""
         return sorted(range(len(self.weights)), key=lambda l: (sensitivity[l], l))

@@ -141,3 +141,40 @@ def test_graph_replayed_evaluations_equal_eager_ones(stacks):
     order = list(range(len(weights)))
     assert graphed.greedy(order, 0.9, graphed.evaluate_by_calls) == gpu.greedy(order, 0.9) == \
         gpu.greedy(order, 0.9, gpu.evaluate_by_calls)
+
+
+def test_noise_sensitivity_matches_the_oracle_and_leaves_the_model_as_it_was(stacks):
+    """E_N of Sec. 3.2.2 on the stack: the drop of the score when one layer's weights carry Gaussian
+    noise of the spread of b-bit rounding.  The same perturbation on the oracle's side (the noise is
+    bit-exact between the two), layer by layer; afterwards the model scores exactly as before."""
+    gpu, orc, weights = stacks
+    top = max(BITS)
+    before = gpu.evaluate([top] * len(weights))
+    lam, seed, b = 0.28867513, 3, 4
+    got = gpu.noise_sensitivity(b, lam, seed)
+    assert gpu.evaluate([top] * len(weights)) == before          # codes and step sizes restored bit for bit
+    base = orc.evaluate([top] * len(weights))
+    for l, w in enumerate(weights):
+        am = oracle.absmax(w, oracle.PER_ROW)
+        noisy = oracle.noise_inject(w, am, b, lam, seed, l, oracle.PER_ROW)
+        am_n = oracle.absmax(noisy, oracle.PER_ROW)
+        _, codes, _ = oracle.fake_quant(noisy, am_n, top, oracle.PER_ROW)
+        keep = orc.wq[l][top]
+        orc.wq[l][top] = (codes, oracle.scale_from_absmax(am_n, top), 8)
+        want = base - orc.evaluate([top] * len(weights))
+        orc.wq[l][top] = keep
+        assert got[l] == pytest.approx(want, abs=2e-5), (l, got[l], want)
+    assert max(got) > 0.0
+
+
+def test_the_end_to_end_demo_runs():
+    """python -m paper_2302_01382_amd.demo on a small stack: sensitivities, orders, both searches, estimates."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-m", "paper_2302_01382_amd.demo", "--layers", "4", "--width", "64", "--rows", "128"],
+                       cwd=root, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=300)
+    assert r.returncode == 0, r.stdout
+    for needle in ("order by E_QE", "order by E_N", "order by Hessian", "bisection", "greedy", "rel.size"):
+        assert needle in r.stdout, r.stdout
