@@ -74,7 +74,17 @@ __global__ __launch_bounds__(kBlock) void absmax_rows(const float* __restrict__ 
   float m = 0.0f;
   if (VEC) {  // cols % 4 == 0 and x 16-byte aligned: every row start is aligned
     const float4* r4 = reinterpret_cast<const float4*>(row);
-    for (int64_t i = (c0 >> 2) + lane; i < (c1 >> 2); i += kWave) {
+    int64_t i = (c0 >> 2) + lane;
+    const int64_t end = c1 >> 2;
+    for (; i + 3 * kWave < end; i += 4 * kWave) {  // four loads in flight per lane
+      const float4 a = load_stream(r4 + i), b = load_stream(r4 + i + kWave), c = load_stream(r4 + i + 2 * kWave),
+                   d = load_stream(r4 + i + 3 * kWave);
+      m = fmaxf(m, fmaxf(fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))),
+                         fmaxf(fmaxf(fabsf(b.x), fabsf(b.y)), fmaxf(fabsf(b.z), fabsf(b.w)))));
+      m = fmaxf(m, fmaxf(fmaxf(fmaxf(fabsf(c.x), fabsf(c.y)), fmaxf(fabsf(c.z), fabsf(c.w))),
+                         fmaxf(fmaxf(fabsf(d.x), fabsf(d.y)), fmaxf(fabsf(d.z), fabsf(d.w)))));
+    }
+    for (; i < end; i += kWave) {
       const float4 a = load_stream(r4 + i);
       m = fmaxf(m, fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))));
     }
