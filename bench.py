@@ -59,6 +59,7 @@ METRIC = "qgemm int8 TOPS (% MFMA peak); quant+error sweep GB/s (% HBM peak)"
 HBM_PEAK_GBS = 8000.0
 INT8_PEAK_TOPS = 5000.0
 ALU_PEAK_TLANEOPS = 256 * 4 * 32 * 2.4e9 / 1e12   # 256 CUs x 4 SIMDs x 32 lanes per clock x 2.4 GHz = 78.6 (157.3 TFLOP/s fp32)
+CLOCK_RAMP_S = 0.03   # untimed device work in front of the sweep's warm-up steps
 LAMBDA = 0.28867513  # 1/sqrt(12): noise with the variance of uniform rounding error of one step
 
 # HBM traffic per main-stream launch of configuration 2 (activation tensor of a layer, averaged
@@ -554,6 +555,14 @@ def bench_sweep_cfg4(torch, mpq, workloads, steps, warmup):
         mpq.quant_error_batch(plan, mpq.PER_TENSOR)
         mpq.quant_error_batch(plan, mpq.PER_ROW)
 
+    # From idle the chip needs some 15 ms of work before its clocks are up (a step is 0.6 ms: with
+    # three warm-up steps the first 20 timed ones run 15 % slower).  Whatever --warmup says, the
+    # device is first kept busy with the same steps for CLOCK_RAMP_S; then the W warm-up steps.
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < CLOCK_RAMP_S:
+        for _ in range(8):
+            step()
+        torch.cuda.synchronize()
     for _ in range(max(warmup, 1)):
         step()
     torch.cuda.synchronize()
@@ -618,6 +627,7 @@ def bench_sweep_cfg4(torch, mpq, workloads, steps, warmup):
     slow = max(("quant_error_batch_per_tensor", "quant_error_batch_per_row"), key=lambda k: us[k])
     return {
         "tensors": len(tensors), "elements": n, "bytes_per_step": 12 * n, "launches_per_step": 5,
+        "clock_ramp_ms_before_warmup": CLOCK_RAMP_S * 1e3,
         "ms_per_step": ms, "gbs": 12.0 * n / ms / 1e6, "frac_of_hbm_peak": 12.0 * n / ms / 1e6 / HBM_PEAK_GBS,
         "call_us": {k: round(v, 2) for k, v in us.items()},
         "same_results_from_two_reads": {"ms_per_step": ms_two, "launches_per_step": 4, "bytes_per_step": 8 * n,
